@@ -1,0 +1,216 @@
+/*
+ * unipool.h -- C ABI of the shared-pool Mixture-of-Experts layer (UniPool),
+ * forward and backward, for one AMD MI355X (gfx950).
+ *
+ * The layer (paper Sec. 4.1, Eq. 2):  FFN_l(x) = sum_{i in Top-k(r_l(x))} g_{l,i}(x) e_i(x),
+ * where the experts e_1..e_M form ONE pool shared by all L layers, every layer has
+ * its own NormRouter r_l (Sec. 4.3, Eq. 7), and a pool-level auxiliary loss balances
+ * expert usage summed over the layers (Sec. 4.2, Eq. 4-6; App. F).
+ *
+ * General conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; tensors are
+ *     row-major and contiguous, last index fastest.  The library allocates nothing
+ *     and keeps no state: weights, gradients, counts and fbar belong to the caller.
+ *   - Scratch memory comes from the caller's workspace `ws` (device pointer, at least
+ *     unipool_workspace_bytes() bytes, 256-byte aligned).  Calls that share a
+ *     workspace must be ordered on one stream.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  No call synchronises with the host or copies to it.
+ *   - Every function returns 0 on success or a negative UNIPOOL_E* code.  Arguments
+ *     are validated before anything is launched; on error nothing has been written.
+ *     unipool_last_error() gives a message for the calling thread's last failure.
+ *   - Same inputs give bitwise the same outputs (no floating-point atomics).
+ *   - dtype UNIPOOL_F32: every floating tensor is float.
+ *     dtype UNIPOOL_BF16: tensors marked "act" below are bfloat16; logits, scores,
+ *     gates, statistics and all weight gradients are float; products accumulate in
+ *     float.  In this mode d_model and d_ff must be multiples of 64.
+ *   - Index tensors are int32.  S = T*k is the number of (token, slot) pairs.
+ *   - Limits: 1 <= k <= 8, k <= E <= 512, T*k < 2^31, sigma > 0.
+ *
+ * Weight storage (Linear convention, [out_features, in_features]):
+ *   w_router  [E, d_model]            z = W h                        (Sec. 4.3)
+ *   w_gate_up [E, 2*d_ff, d_model]    rows [0, d_ff) of expert e are W_gate,e,
+ *                                     rows [d_ff, 2 d_ff) are W_up,e
+ *   w_down    [E, d_model, d_ff]      e(x) = W_down ( silu(W_gate x) * (W_up x) )
+ * Weight gradients have the same shapes, in float.
+ */
+#ifndef UNIPOOL_H
+#define UNIPOOL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define UNIPOOL_OK          0
+#define UNIPOOL_EINVAL     -1   /* NULL/invalid argument, unsupported shape or alignment */
+#define UNIPOOL_EWORKSPACE -2   /* workspace missing or too small */
+#define UNIPOOL_ELAUNCH    -3   /* the HIP runtime reported an error */
+
+#define UNIPOOL_F32  0
+#define UNIPOOL_BF16 1
+
+typedef struct unipool_shape {
+    int32_t T;          /* tokens in this layer call */
+    int32_t d_model;    /* d */
+    int32_t d_ff;       /* f, hidden width of one expert */
+    int32_t E;          /* pool size M */
+    int32_t k;          /* experts per token */
+    int32_t L;          /* layers sharing the pool (used by unipool_pool_aux_loss only) */
+    int32_t dtype;      /* UNIPOOL_F32 or UNIPOOL_BF16 */
+    float sigma;        /* NormRouter scale of THIS layer (learnable, init 1; Eq. 7) */
+    float c;            /* NormRouter calibration constant (App. G); a plain input */
+    float eps;          /* NormRouter epsilon, added outside the norm (Eq. 7) */
+    float alpha_pool;   /* pool auxiliary loss coefficient (Eq. 5) */
+} unipool_shape;
+
+/* Bytes of workspace that is enough for every entry point at this shape. */
+size_t unipool_workspace_bytes(const unipool_shape* shape);
+
+/* Message for the last error returned on the calling thread (never NULL). */
+const char* unipool_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int unipool_version(void);
+
+/*
+ * Router of one layer (Sec. 4.3, Eq. 7 and the top-k paragraph).
+ *   z = x W^T (float accumulate);  n = ||z||_2;  s_i = sigma c max(0, z_i/(n+eps));
+ *   topk_idx[t, :] = the k experts with the largest logits, in descending order,
+ *   exact ties to the lower index;  topk_gate[t, j] = s_{t, topk_idx[t,j]} (raw score).
+ *   counts[i] = number of (t, j) with topk_idx[t,j] == i;  psum[i] = sum_t s_{t,i} over
+ *   ALL experts (the statistics f and P of Sec. 4.2 before normalisation).
+ * in : x [T, d] act;  w_router [E, d] act
+ * out: topk_idx [T, k] int32;  topk_gate [T, k] float;  logits [T, E] float (saved
+ *      for the backward pass; may be NULL);  counts [E] int32;  psum [E] float.
+ * counts and psum are overwritten, not accumulated.
+ */
+int unipool_route(const unipool_shape* shape, const void* x, const void* w_router,
+                  int32_t* topk_idx, float* topk_gate, float* logits,
+                  int32_t* counts, float* psum,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward of the router (derivative of Eq. 7 and of z = W h; App. F: the pool
+ * loss reaches parameters only through the scores).
+ *   ds_{t,i} = aux_coef[i] (all i; omitted if aux_coef is NULL) + dgate[t,j] for i = topk_idx[t,j]
+ *   d_sigma  = sum_{t,i} ds_{t,i} c max(0, zhat_{t,i});  dzhat = ds sigma c [zhat > 0]
+ *   dz_j     = dzhat_j/(n+eps) - z_j <dzhat, z> / (n (n+eps)^2)
+ *   d_w_router = dz^T x;   dx += dz W  (dx_accumulate != 0) or dx = dz W.
+ * in : x, w_router as in unipool_route;  logits [T, E] float from unipool_route;
+ *      topk_idx [T, k];  dgate [T, k] float;  aux_coef [E] float or NULL.
+ * out: d_w_router [E, d] float (overwritten);  d_sigma [1] float (overwritten);
+ *      dx [T, d] act (accumulated into or overwritten, see dx_accumulate).
+ */
+int unipool_route_bwd(const unipool_shape* shape, const void* x, const void* w_router,
+                      const float* logits, const int32_t* topk_idx, const float* dgate,
+                      const float* aux_coef, float* d_w_router, float* d_sigma,
+                      void* dx, int dx_accumulate,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Dispatch: expert-contiguous copy of the tokens (the grouping a grouped GEMM needs;
+ * Table 7 only says that grouped GEMM is used, the row order is this library's).
+ *   expert_offsets = exclusive prefix sum of counts, expert_offsets[E] = S;
+ *   the rows of expert e are expert_offsets[e] .. expert_offsets[e+1]-1 and hold the
+ *   tokens that selected e in ascending token order;
+ *   row_of_slot[t, j] = row of token t for its j-th expert;  slot_of_row[row] = t*k + j;
+ *   x_perm[row_of_slot[t,j], :] = x[t, :].
+ * in : x [T, d] act;  topk_idx [T, k];  counts [E] (from unipool_route)
+ * out: x_perm [S, d] act;  expert_offsets [E+1];  row_of_slot [T, k];  slot_of_row [S].
+ */
+int unipool_permute(const unipool_shape* shape, const void* x, const int32_t* topk_idx,
+                    const int32_t* counts, void* x_perm, int32_t* expert_offsets,
+                    int32_t* row_of_slot, int32_t* slot_of_row,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Pool experts on their row groups (Eq. 2's e_i; SwiGLU FFN, Table 6 caption).
+ * For every expert e with rows R_e:  A = X_e W_gate,e^T;  B = X_e W_up,e^T;
+ *   H = silu(A) * B;  Y = H W_down,e^T.   Experts without rows cost nothing.
+ * in : x_perm [S, d] act;  expert_offsets [E+1];  w_gate_up, w_down (see top).
+ * out: act_a, act_b, act_h [S, f] act (saved for the backward pass);  y_perm [S, d] act.
+ */
+int unipool_expert_ffn_fwd(const unipool_shape* shape, const void* x_perm,
+                           const int32_t* expert_offsets, const void* w_gate_up,
+                           const void* w_down, void* act_a, void* act_b, void* act_h,
+                           void* y_perm, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward of the pool experts for one layer.
+ *   dH = dY W_down;  dA = dH * B * silu'(A);  dB = dH * silu(A);
+ *   dX_perm = dA W_gate + dB W_up;
+ *   d_w_down[e]    += dY_e^T H_e;   d_w_gate_up[e] += [dA_e | dB_e]^T X_e.
+ * The pool is shared: every layer adds into the same float gradient buffers, which
+ * the caller zeroes once per step (Sec. 3: each expert gathers gradients of L layers).
+ * Experts without rows leave their gradient untouched.
+ * in : dy_perm [S, d] act;  x_perm, act_a, act_b, act_h, expert_offsets, weights as above.
+ * out: dx_perm [S, d] act;  d_act [S, 2f] act = [dA | dB] (also scratch for the weight
+ *      gradient);  d_w_gate_up [E, 2f, d] float and d_w_down [E, d, f] float, accumulated.
+ *      d_w_gate_up and d_w_down may both be NULL: then only dx_perm and d_act are made
+ *      (the weight gradient can be taken later by unipool_expert_wgrad).
+ */
+int unipool_expert_ffn_bwd(const unipool_shape* shape, const void* dy_perm, const void* x_perm,
+                           const void* act_a, const void* act_b, const void* act_h,
+                           const int32_t* expert_offsets, const void* w_gate_up,
+                           const void* w_down, void* dx_perm, void* d_act,
+                           float* d_w_gate_up, float* d_w_down,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Weight gradient of the pool for n_layers layer calls at once.  Because the pool is
+ * shared, the rows an expert received in different layers extend one reduction:
+ *   d_w_gate_up[e] (+)= sum_l [dA|dB]^(l)_e^T X^(l)_e;   d_w_down[e] (+)= sum_l dY^(l)_e^T H^(l)_e.
+ * The result equals n_layers calls of unipool_expert_ffn_bwd's accumulation.
+ * in : device arrays of n_layers device pointers each: x_perm_l, d_act_l, act_h_l,
+ *      dy_perm_l (tensors as in unipool_expert_ffn_bwd) and expert_offsets_l ([E+1] each).
+ * out: d_w_gate_up, d_w_down float; accumulate != 0 adds to them, 0 overwrites them
+ *      (experts with no rows in any layer are then set to zero).
+ */
+int unipool_expert_wgrad(const unipool_shape* shape, int n_layers,
+                         const void* const* x_perm_l, const void* const* d_act_l,
+                         const void* const* act_h_l, const void* const* dy_perm_l,
+                         const int32_t* const* expert_offsets_l,
+                         float* d_w_gate_up, float* d_w_down, int accumulate,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Gate-weighted combine (Eq. 2):  out[t] = sum_j gate[t,j] * y_perm[row_of_slot[t,j]],
+ * summed in slot order with float accumulation.  gate == NULL means unit gates, which
+ * is the backward of unipool_permute (dX[t] = sum_j dX_perm[row_of_slot[t,j]]).
+ * in : y_perm [S, d] act;  row_of_slot [T, k];  gate [T, k] float or NULL
+ * out: out [T, d] act.
+ */
+int unipool_combine(const unipool_shape* shape, const void* y_perm, const int32_t* row_of_slot,
+                    const float* gate, void* out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward of the combine:  dy_perm[row_of_slot[t,j]] = gate[t,j] * dout[t];
+ *                           dgate[t,j] = <dout[t], y_perm[row_of_slot[t,j]]>.
+ * in : dout [T, d] act;  y_perm [S, d] act;  row_of_slot [T, k];  gate [T, k] float
+ * out: dy_perm [S, d] act;  dgate [T, k] float.
+ */
+int unipool_combine_bwd(const unipool_shape* shape, const void* dout, const void* y_perm,
+                        const int32_t* row_of_slot, const float* gate, void* dy_perm,
+                        float* dgate, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Pool-level auxiliary loss over the L layers that share the pool (Sec. 4.2).
+ *   pool_counts[i] = sum_l counts[l,i];   fbar_out[i] = pool_counts[i] / (L T k)   (Eq. 4)
+ *   fbar = fbar_in if given (one-step-behind statistic of App. F) else fbar_out
+ *   loss = alpha_pool M sum_i fbar_i Pbar_i,  Pbar_i = (1/(L T)) sum_l psum[l,i]   (Eq. 5)
+ *   aux_coef[i] = alpha_pool M fbar_i / (L T)  = d loss / d s^(l)_{t,i}             (Eq. 6)
+ * fbar is a constant for differentiation (App. F).
+ * in : counts [L, E] int32;  psum [L, E] float;  fbar_in [E] float or NULL
+ * out: pool_counts [E] int32;  fbar_out [E] float;  loss [1] float;  aux_coef [E] float.
+ */
+int unipool_pool_aux_loss(const unipool_shape* shape, const int32_t* counts, const float* psum,
+                          const float* fbar_in, int32_t* pool_counts, float* fbar_out,
+                          float* loss, float* aux_coef, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UNIPOOL_H */

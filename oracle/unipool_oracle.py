@@ -56,13 +56,15 @@ def topk_select(z, k):
     return order[..., :k].astype(np.int32)
 
 
-def route(x, w_router, k, sigma, c, eps):
+def route(x, w_router, k, sigma, c, eps, idx=None):
     """Router of one layer: logits, scores, top-k, gates and the layer statistics
     the auxiliary losses need (Sec. 4.2: token counts per expert and the sum of
-    routing scores per expert over the tokens of the layer)."""
+    routing scores per expert over the tokens of the layer).
+    `idx` replaces the selection (used by tests to impose the other, equally
+    valid choice on tokens whose logits tie within rounding)."""
     z = router_logits(x, w_router)
     s, n = norm_router_scores(z, sigma, c, eps)
-    idx = topk_select(z, k)
+    idx = topk_select(z, k) if idx is None else np.asarray(idx, dtype=np.int32)
     gate = np.take_along_axis(s, idx.astype(np.int64), axis=1)
     E = z.shape[1]
     counts = np.bincount(idx.ravel(), minlength=E).astype(np.int64)
@@ -155,10 +157,10 @@ def combine(y_perm, row_of_slot, gate=None):
     return out
 
 
-def moe_layer_fwd(x, w_router, w_gate, w_up, w_down, k, sigma, c, eps):
+def moe_layer_fwd(x, w_router, w_gate, w_up, w_down, k, sigma, c, eps, idx=None):
     """Eq. 2 for one layer, through routing, dispatch, experts and combine."""
     E = w_gate.shape[0]
-    r = route(x, w_router, k, sigma, c, eps)
+    r = route(x, w_router, k, sigma, c, eps, idx)
     offsets, row_of_slot, slot_of_row = permutation(r["idx"], E)
     x_perm = permute_rows(np.asarray(x, F64), slot_of_row, k)
     a, b, h, y = expert_ffn_fwd(x_perm, offsets, w_gate, w_up, w_down)
@@ -302,12 +304,13 @@ def moe_layer_bwd(fw, x, w_router, w_gate, w_up, w_down, dout, aux_coef, k, sigm
 # Whole step over the L layers that share the pool
 # ---------------------------------------------------------------------------
 def pool_step(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps, alpha,
-              fbar_in=None):
+              fbar_in=None, idxs=None):
     """Forward of all layers, pool loss (Eq. 5), backward of all layers.
     Expert weight gradients are summed over the layers (one shared pool)."""
     L = len(xs)
     T = xs[0].shape[0]
-    fws = [moe_layer_fwd(xs[l], w_routers[l], w_gate, w_up, w_down, k, sigmas[l], c, eps)
+    fws = [moe_layer_fwd(xs[l], w_routers[l], w_gate, w_up, w_down, k, sigmas[l], c, eps,
+                         None if idxs is None else idxs[l])
            for l in range(L)]
     counts = np.stack([fw["counts"] for fw in fws])
     psum = np.stack([fw["psum"] for fw in fws])

@@ -1,0 +1,335 @@
+// C ABI of the UniPool library: argument checks, workspace carving and kernel dispatch.
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "kernels.h"
+
+namespace unipool {
+
+namespace {
+thread_local char g_err[512] = "no error";
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// UNIPOOL_FORCE_NAIVE=1 sends bfloat16 contractions to the plain one-thread-per-element kernels
+// (a debugging aid; still device code).
+bool force_naive() {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("UNIPOOL_FORCE_NAIVE");
+        v = (e && e[0] == '1') ? 1 : 0;
+    }
+    return v == 1;
+}
+
+__global__ void fill_zero_kernel(uint32_t* p, size_t words) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < words) p[i] = 0u;
+}
+
+__global__ void set_ptrs_kernel(void** table, const void* p0, const void* p1, const void* p2,
+                                const void* p3, const void* p4) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        table[0] = const_cast<void*>(p0);
+        table[1] = const_cast<void*>(p1);
+        table[2] = const_cast<void*>(p2);
+        table[3] = const_cast<void*>(p3);
+        table[4] = const_cast<void*>(p4);
+    }
+}
+}  // namespace
+
+int set_error(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_hip(hipError_t e, const char* what) {
+    if (e == hipSuccess) return UNIPOOL_OK;
+    return set_error(UNIPOOL_ELAUNCH, "%s: %s", what, hipGetErrorString(e));
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
+    const size_t words = bytes / 4;
+    if (words == 0) return hipSuccess;
+    fill_zero_kernel<<<(unsigned)((words + 255) / 256), 256, 0, st>>>((uint32_t*)p, words);
+    return hipGetLastError();
+}
+
+hipError_t launch_set_ptrs(void** table, const void* p0, const void* p1, const void* p2,
+                           const void* p3, const void* p4, hipStream_t st) {
+    set_ptrs_kernel<<<1, 64, 0, st>>>(table, p0, p1, p2, p3, p4);
+    return hipGetLastError();
+}
+
+WsLayout ws_layout(const unipool_shape& s) {
+    WsLayout w;
+    const size_t T = (size_t)s.T, E = (size_t)s.E, d = (size_t)s.d_model;
+    const size_t S = T * (size_t)s.k;
+    const size_t rblocks = (T + kRouterTokensPerBlock - 1) / kRouterTokensPerBlock;
+    const size_t act = s.dtype == UNIPOOL_BF16 ? 2 : 4;
+    size_t o = 0;
+    w.zeros = o;       o += 256;
+    w.tile_meta = o;   o += align_up((4096 + 4 * (S / 256 + E + T / 256 + 16)) * sizeof(int32_t));
+    w.chunk_hist = o;  o += align_up(((T + 63) / 64) * E * sizeof(int32_t));
+    w.psum_part = o;   o += align_up(rblocks * E * sizeof(float));
+    w.dsigma_part = o; o += align_up(rblocks * E * sizeof(int32_t));   // also holds count partials
+    w.dz = o;          o += align_up(T * E * (act > 4 ? act : 4));     // logits (float) or dz
+    w.ptr_tab = o;     o += 256;
+    w.wpart = o;       o += align_up((size_t)kRouteBwdSplit * E * d * sizeof(float));
+    w.total = o;
+    return w;
+}
+
+namespace {
+
+int validate(const unipool_shape* s, const char* fn) {
+    if (!s) return set_error(UNIPOOL_EINVAL, "%s: shape is NULL", fn);
+    if (s->dtype != UNIPOOL_F32 && s->dtype != UNIPOOL_BF16)
+        return set_error(UNIPOOL_EINVAL, "%s: dtype %d is neither UNIPOOL_F32 nor UNIPOOL_BF16", fn, s->dtype);
+    if (s->T < 1 || s->d_model < 1 || s->d_ff < 1)
+        return set_error(UNIPOOL_EINVAL, "%s: T, d_model, d_ff must be positive (T=%d d=%d f=%d)", fn, s->T,
+                         s->d_model, s->d_ff);
+    if (s->E < 1 || s->E > kMaxE) return set_error(UNIPOOL_EINVAL, "%s: E=%d outside [1, %d]", fn, s->E, kMaxE);
+    if (s->k < 1 || s->k > kMaxK || s->k > s->E)
+        return set_error(UNIPOOL_EINVAL, "%s: k=%d outside [1, min(%d, E=%d)]", fn, s->k, kMaxK, s->E);
+    if ((long long)s->T * s->k >= (1LL << 31))
+        return set_error(UNIPOOL_EINVAL, "%s: T*k does not fit int32", fn);
+    if (s->dtype == UNIPOOL_BF16 && (s->d_model % 64 != 0 || s->d_ff % 64 != 0))
+        return set_error(UNIPOOL_EINVAL, "%s: bfloat16 mode needs d_model and d_ff to be multiples of 64 (d=%d f=%d)",
+                         fn, s->d_model, s->d_ff);
+    if (!(s->sigma > 0.f)) return set_error(UNIPOOL_EINVAL, "%s: sigma must be positive", fn);
+    if (!(s->eps >= 0.f)) return set_error(UNIPOOL_EINVAL, "%s: eps must be non-negative", fn);
+    return UNIPOOL_OK;
+}
+
+int need_ws(const unipool_shape* s, void* ws, size_t ws_bytes, const char* fn) {
+    if (!ws) return set_error(UNIPOOL_EWORKSPACE, "%s: workspace is NULL", fn);
+    if (((uintptr_t)ws & 255) != 0) return set_error(UNIPOOL_EWORKSPACE, "%s: workspace is not 256-byte aligned", fn);
+    const size_t need = ws_layout(*s).total;
+    if (ws_bytes < need)
+        return set_error(UNIPOOL_EWORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, ws_bytes, need);
+    return UNIPOOL_OK;
+}
+
+#define REQUIRE_PTR(p)                                                                  \
+    if (!(p)) return unipool::set_error(UNIPOOL_EINVAL, "%s: argument %s is NULL", __func__, #p)
+#define PROLOGUE()                                                            \
+    {                                                                         \
+        int rc_ = unipool::validate(shape, __func__);                         \
+        if (rc_) return rc_;                                                  \
+    }
+#define NEED_WS()                                                             \
+    {                                                                         \
+        int rc_ = unipool::need_ws(shape, ws, ws_bytes, __func__);            \
+        if (rc_) return rc_;                                                  \
+    }
+
+}  // namespace
+}  // namespace unipool
+
+using namespace unipool;
+
+extern "C" {
+
+size_t unipool_workspace_bytes(const unipool_shape* shape) {
+    if (validate(shape, __func__) != UNIPOOL_OK) return 0;
+    return ws_layout(*shape).total;
+}
+
+const char* unipool_last_error(void) { return g_err; }
+
+int unipool_version(void) { return 100; }
+
+int unipool_route(const unipool_shape* shape, const void* x, const void* w_router,
+                  int32_t* topk_idx, float* topk_gate, float* logits, int32_t* counts, float* psum,
+                  void* ws, size_t ws_bytes, void* stream) {
+    PROLOGUE();
+    REQUIRE_PTR(x); REQUIRE_PTR(w_router); REQUIRE_PTR(topk_idx); REQUIRE_PTR(topk_gate);
+    REQUIRE_PTR(counts); REQUIRE_PTR(psum);
+    NEED_WS();
+    const WsLayout w = ws_layout(*shape);
+    char* base = (char*)ws;
+    hipStream_t st = (hipStream_t)stream;
+    float* z = logits ? logits : (float*)(base + w.dz);
+    hipError_t e;
+    if (mfma_router_supported(*shape) && !force_naive())
+        e = mfma_logits(*shape, x, w_router, z, (int32_t*)(base + w.tile_meta), st);
+    else
+        e = naive_logits(*shape, x, w_router, z, st);
+    if (e != hipSuccess) return check_hip(e, "unipool_route: logits");
+    e = launch_route_score_topk(*shape, z, topk_idx, topk_gate, counts, psum,
+                                (int32_t*)(base + w.dsigma_part), (float*)(base + w.psum_part), st);
+    return check_hip(e, "unipool_route: score/top-k");
+}
+
+int unipool_route_bwd(const unipool_shape* shape, const void* x, const void* w_router,
+                      const float* logits, const int32_t* topk_idx, const float* dgate,
+                      const float* aux_coef, float* d_w_router, float* d_sigma, void* dx,
+                      int dx_accumulate, void* ws, size_t ws_bytes, void* stream) {
+    PROLOGUE();
+    REQUIRE_PTR(x); REQUIRE_PTR(w_router); REQUIRE_PTR(logits); REQUIRE_PTR(topk_idx);
+    REQUIRE_PTR(dgate); REQUIRE_PTR(d_w_router); REQUIRE_PTR(d_sigma); REQUIRE_PTR(dx);
+    NEED_WS();
+    const WsLayout w = ws_layout(*shape);
+    char* base = (char*)ws;
+    hipStream_t st = (hipStream_t)stream;
+    void* dz = base + w.dz;
+    hipError_t e = launch_route_bwd_dz(*shape, logits, topk_idx, dgate, aux_coef, dz,
+                                       (float*)(base + w.dsigma_part), d_sigma, st);
+    if (e != hipSuccess) return check_hip(e, "unipool_route_bwd: dz");
+    if (mfma_router_supported(*shape) && !force_naive()) {
+        e = launch_fill_zero(base + w.zeros, 256, st);
+        if (e != hipSuccess) return check_hip(e, "unipool_route_bwd: zero page");
+        e = mfma_route_bwd_mm(*shape, x, w_router, dz, d_w_router, dx, dx_accumulate,
+                              (int32_t*)(base + w.tile_meta), (float*)(base + w.wpart),
+                              base + w.zeros, st);
+    } else {
+        e = naive_route_bwd_mm(*shape, x, w_router, dz, d_w_router, dx, dx_accumulate, st);
+    }
+    return check_hip(e, "unipool_route_bwd: contractions");
+}
+
+int unipool_permute(const unipool_shape* shape, const void* x, const int32_t* topk_idx,
+                    const int32_t* counts, void* x_perm, int32_t* expert_offsets,
+                    int32_t* row_of_slot, int32_t* slot_of_row, void* ws, size_t ws_bytes,
+                    void* stream) {
+    PROLOGUE();
+    REQUIRE_PTR(x); REQUIRE_PTR(topk_idx); REQUIRE_PTR(counts); REQUIRE_PTR(x_perm);
+    REQUIRE_PTR(expert_offsets); REQUIRE_PTR(row_of_slot); REQUIRE_PTR(slot_of_row);
+    NEED_WS();
+    const WsLayout w = ws_layout(*shape);
+    hipError_t e = launch_permute(*shape, x, topk_idx, counts, x_perm, expert_offsets, row_of_slot,
+                                  slot_of_row, (int32_t*)((char*)ws + w.chunk_hist),
+                                  (hipStream_t)stream);
+    return check_hip(e, "unipool_permute");
+}
+
+int unipool_expert_ffn_fwd(const unipool_shape* shape, const void* x_perm,
+                           const int32_t* expert_offsets, const void* w_gate_up, const void* w_down,
+                           void* act_a, void* act_b, void* act_h, void* y_perm, void* ws,
+                           size_t ws_bytes, void* stream) {
+    PROLOGUE();
+    REQUIRE_PTR(x_perm); REQUIRE_PTR(expert_offsets); REQUIRE_PTR(w_gate_up); REQUIRE_PTR(w_down);
+    REQUIRE_PTR(act_a); REQUIRE_PTR(act_b); REQUIRE_PTR(act_h); REQUIRE_PTR(y_perm);
+    NEED_WS();
+    const WsLayout w = ws_layout(*shape);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (mfma_ffn_supported(*shape) && !force_naive())
+        e = mfma_ffn_fwd(*shape, x_perm, expert_offsets, w_gate_up, w_down, act_a, act_b, act_h,
+                         y_perm, (int32_t*)((char*)ws + w.tile_meta), st);
+    else
+        e = naive_ffn_fwd(*shape, x_perm, expert_offsets, w_gate_up, w_down, act_a, act_b, act_h,
+                          y_perm, st);
+    return check_hip(e, "unipool_expert_ffn_fwd");
+}
+
+int unipool_expert_ffn_bwd(const unipool_shape* shape, const void* dy_perm, const void* x_perm,
+                           const void* act_a, const void* act_b, const void* act_h,
+                           const int32_t* expert_offsets, const void* w_gate_up, const void* w_down,
+                           void* dx_perm, void* d_act, float* d_w_gate_up, float* d_w_down,
+                           void* ws, size_t ws_bytes, void* stream) {
+    PROLOGUE();
+    REQUIRE_PTR(dy_perm); REQUIRE_PTR(x_perm); REQUIRE_PTR(act_a); REQUIRE_PTR(act_b);
+    REQUIRE_PTR(expert_offsets); REQUIRE_PTR(w_gate_up); REQUIRE_PTR(w_down); REQUIRE_PTR(dx_perm);
+    REQUIRE_PTR(d_act);
+    if ((d_w_gate_up == nullptr) != (d_w_down == nullptr))
+        return set_error(UNIPOOL_EINVAL, "%s: d_w_gate_up and d_w_down must both be given or both be NULL", __func__);
+    if (d_w_gate_up) REQUIRE_PTR(act_h);
+    NEED_WS();
+    const WsLayout w = ws_layout(*shape);
+    char* base = (char*)ws;
+    hipStream_t st = (hipStream_t)stream;
+    const bool mfma = mfma_ffn_supported(*shape) && !force_naive();
+    hipError_t e;
+    if (mfma)
+        e = mfma_ffn_dgrad(*shape, dy_perm, act_a, act_b, expert_offsets, w_gate_up, w_down, dx_perm,
+                           d_act, (int32_t*)(base + w.tile_meta), st);
+    else
+        e = naive_ffn_dgrad(*shape, dy_perm, act_a, act_b, expert_offsets, w_gate_up, w_down, dx_perm,
+                            d_act, st);
+    if (e != hipSuccess) return check_hip(e, "unipool_expert_ffn_bwd: dgrad");
+    if (!d_w_gate_up) return UNIPOOL_OK;
+    void** tab = (void**)(base + w.ptr_tab);
+    e = launch_set_ptrs(tab, x_perm, d_act, act_h, dy_perm, expert_offsets, st);
+    if (e != hipSuccess) return check_hip(e, "unipool_expert_ffn_bwd: pointer table");
+    if (mfma) {
+        e = launch_fill_zero(base + w.zeros, 256, st);
+        if (e != hipSuccess) return check_hip(e, "unipool_expert_ffn_bwd: zero page");
+        e = mfma_ffn_wgrad(*shape, 1, tab + 0, tab + 1, tab + 2, tab + 3,
+                           (const int32_t* const*)(tab + 4), d_w_gate_up, d_w_down, 1,
+                           base + w.zeros, st);
+    } else {
+        e = naive_ffn_wgrad(*shape, 1, tab + 0, tab + 1, tab + 2, tab + 3,
+                            (const int32_t* const*)(tab + 4), d_w_gate_up, d_w_down, 1, st);
+    }
+    return check_hip(e, "unipool_expert_ffn_bwd: wgrad");
+}
+
+int unipool_expert_wgrad(const unipool_shape* shape, int n_layers, const void* const* x_perm_l,
+                         const void* const* d_act_l, const void* const* act_h_l,
+                         const void* const* dy_perm_l, const int32_t* const* expert_offsets_l,
+                         float* d_w_gate_up, float* d_w_down, int accumulate, void* ws,
+                         size_t ws_bytes, void* stream) {
+    PROLOGUE();
+    if (n_layers < 1) return set_error(UNIPOOL_EINVAL, "%s: n_layers=%d must be positive", __func__, n_layers);
+    REQUIRE_PTR(x_perm_l); REQUIRE_PTR(d_act_l); REQUIRE_PTR(act_h_l); REQUIRE_PTR(dy_perm_l);
+    REQUIRE_PTR(expert_offsets_l); REQUIRE_PTR(d_w_gate_up); REQUIRE_PTR(d_w_down);
+    NEED_WS();
+    const WsLayout w = ws_layout(*shape);
+    char* base = (char*)ws;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (mfma_ffn_supported(*shape) && !force_naive()) {
+        e = launch_fill_zero(base + w.zeros, 256, st);
+        if (e != hipSuccess) return check_hip(e, "unipool_expert_wgrad: zero page");
+        e = mfma_ffn_wgrad(*shape, n_layers, x_perm_l, d_act_l, act_h_l, dy_perm_l, expert_offsets_l,
+                           d_w_gate_up, d_w_down, accumulate, base + w.zeros, st);
+    } else {
+        e = naive_ffn_wgrad(*shape, n_layers, x_perm_l, d_act_l, act_h_l, dy_perm_l, expert_offsets_l,
+                            d_w_gate_up, d_w_down, accumulate, st);
+    }
+    return check_hip(e, "unipool_expert_wgrad");
+}
+
+int unipool_combine(const unipool_shape* shape, const void* y_perm, const int32_t* row_of_slot,
+                    const float* gate, void* out, void* ws, size_t ws_bytes, void* stream) {
+    PROLOGUE();
+    REQUIRE_PTR(y_perm); REQUIRE_PTR(row_of_slot); REQUIRE_PTR(out);
+    (void)ws; (void)ws_bytes;
+    return check_hip(launch_combine(*shape, y_perm, row_of_slot, gate, out, (hipStream_t)stream),
+                     "unipool_combine");
+}
+
+int unipool_combine_bwd(const unipool_shape* shape, const void* dout, const void* y_perm,
+                        const int32_t* row_of_slot, const float* gate, void* dy_perm, float* dgate,
+                        void* ws, size_t ws_bytes, void* stream) {
+    PROLOGUE();
+    REQUIRE_PTR(dout); REQUIRE_PTR(y_perm); REQUIRE_PTR(row_of_slot); REQUIRE_PTR(gate);
+    REQUIRE_PTR(dy_perm); REQUIRE_PTR(dgate);
+    (void)ws; (void)ws_bytes;
+    return check_hip(launch_combine_bwd(*shape, dout, y_perm, row_of_slot, gate, dy_perm, dgate,
+                                        (hipStream_t)stream),
+                     "unipool_combine_bwd");
+}
+
+int unipool_pool_aux_loss(const unipool_shape* shape, const int32_t* counts, const float* psum,
+                          const float* fbar_in, int32_t* pool_counts, float* fbar_out, float* loss,
+                          float* aux_coef, void* ws, size_t ws_bytes, void* stream) {
+    PROLOGUE();
+    if (shape->L < 1) return set_error(UNIPOOL_EINVAL, "%s: L=%d must be positive", __func__, shape->L);
+    REQUIRE_PTR(counts); REQUIRE_PTR(psum); REQUIRE_PTR(pool_counts); REQUIRE_PTR(fbar_out);
+    REQUIRE_PTR(loss); REQUIRE_PTR(aux_coef);
+    (void)ws; (void)ws_bytes;
+    return check_hip(launch_pool_aux_loss(*shape, counts, psum, fbar_in, pool_counts, fbar_out, loss,
+                                          aux_coef, (hipStream_t)stream),
+                     "unipool_pool_aux_loss");
+}
+
+}  // extern "C"

@@ -1,0 +1,787 @@
+// bfloat16 grouped GEMMs on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), float accumulate.
+//
+// Two kernels cover every dense contraction of the layer:
+//
+//   gemm_xw  : C[rows of e, N] = X[rows of e, K] * W_e          (row-grouped; forward, dgrad, router)
+//              X is K-contiguous.  W_e is either [N][K] (K-contiguous) or [K][N] (N-contiguous).
+//   gemm_ptq : out[e][i][j] (+)= sum_rows P[row][i] * Q[row][j]  (reduction over the rows of e,
+//              possibly chained over several layers; weight gradients)
+//
+// Common structure
+//   * 256 threads = 4 wavefronts, one workgroup per CU, accumulators in the upper register file.
+//   * Operand tiles go global -> LDS directly (global_load_lds_dwordx4), NS stages deep, one
+//     barrier per K step.  The loads are issued through inline assembly so that the wait counts
+//     are ours: the compiler would otherwise wait for every outstanding load before any LDS read.
+//   * LDS tiles hold 16-byte chunks in XOR-swizzled positions; a direct-to-LDS load writes 64
+//     consecutive chunks, so the swizzle is applied on the global address of each lane.
+//   * Operands whose reduction index is the strided one in memory are read from LDS with
+//     ds_read_b64_tr_b16, which hands each lane four consecutive reduction indices of one column.
+//   * The weight fragment is the MFMA A operand and the activation fragment the B operand, so a
+//     lane ends up with four consecutive output columns of one row: results are staged through
+//     LDS and leave the CU as 16-byte row segments.
+//   * Row groups come from a device-side tile table; nothing is read back to the host.  Tiles are
+//     walked in an order that keeps the tiles of one expert on one XCD (workgroup ids are dealt
+//     round-robin to the 8 XCDs, each of which has its own L2).
+#include "kernels.h"
+
+namespace unipool {
+
+namespace {
+
+constexpr int EPI_STORE = 0;       // bf16 store (optionally added to the destination)
+constexpr int EPI_SWIGLU_FWD = 1;  // tile = [gate | up] columns; writes A, B, H = silu(A)*B
+constexpr int EPI_SWIGLU_BWD = 2;  // acc = dH; reads A, B; writes dA | dB
+constexpr int EPI_F32 = 3;         // float store
+
+constexpr int kNumXcd = 8;
+
+struct GemmArgs {
+    const bf16* X;
+    int ldx;
+    const bf16* W;
+    long long w_stride;   // elements between experts
+    int ldw;
+    int K, N;             // reduction length; number of output columns (per half for SWIGLU_FWD)
+    int n_tiles_n;
+    const int32_t* tile_meta;
+    void* out0;
+    void* out1;
+    void* out2;
+    int ldo;
+    int add;              // EPI_STORE: add to the destination
+    const bf16* aux_a;
+    const bf16* aux_b;
+    int up_rows;          // EPI_SWIGLU_FWD: row offset of the up projection inside W_e (= d_ff)
+    int group_m;          // row tiles walked together
+};
+
+// ---------------------------------------------------------------------------------------------
+// low-level helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void glds16(const void* gptr, unsigned lds_addr) {
+    // 64 lanes x 16 bytes -> LDS[lds_addr + 16*lane]; lds_addr must be wave-uniform.
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(base)
+                 : "memory", "m0");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    // gfx9 encoding: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14; other counters untouched
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
+    return (unsigned)(size_t)(__attribute__((address_space(3))) const char*)p;
+}
+
+__device__ __forceinline__ bf16x8 lds_read16(const char* p) {
+    return *reinterpret_cast<const bf16x8*>(p);
+}
+
+__device__ __forceinline__ bf16x8 lds_read_tr8(const char* p0, const char* p1) {
+    typedef __attribute__((address_space(3))) short4v* lp;
+    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p0);
+    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p1);
+    union { short4v s[2]; bf16x8 v; } u;
+    u.s[0] = lo;
+    u.s[1] = hi;
+    return u.v;
+}
+
+// K-contiguous tile: rows of BK elements, CPR = BK/8 chunks per row.
+template <int BK> struct KTile {
+    static constexpr int CPR = BK / 8;
+    static constexpr int RP = 256 / (BK * 2);   // rows per 256 bytes
+    __device__ static __forceinline__ int swz(int row) { return (row / RP) & (CPR - 1); }
+    // byte offset of logical chunk cc of row
+    __device__ static __forceinline__ int off(int row, int cc) {
+        return (row * CPR + (cc ^ swz(row))) * 16;
+    }
+};
+
+// N-contiguous tile: BK rows of BC elements, CPR = BC/8 chunks per row (>= 16).
+template <int BC> struct NTile {
+    static constexpr int CPR = BC / 8;
+    __device__ static __forceinline__ int swz(int krow) { return (krow & 3) << 2; }
+    __device__ static __forceinline__ int off(int krow, int col) {
+        return (krow * CPR + ((col >> 3) ^ swz(krow))) * 16 + (col & 7) * 2;
+    }
+    // fragment of 32 columns starting at col0, reduction indices ks*16 .. ks*16+15
+    __device__ static __forceinline__ bf16x8 frag(const char* base, int ks, int col0, int lane) {
+        const int krow = ks * 16 + 8 * (lane >> 5) + ((lane & 15) >> 2);
+        const int col = col0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        return lds_read_tr8(base + off(krow, col), base + off(krow + 4, col));
+    }
+};
+
+__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
+    union { bf16 h[4]; uint2 u; } p;
+    p.h[0] = (bf16)a;
+    p.h[1] = (bf16)b;
+    p.h[2] = (bf16)c;
+    p.h[3] = (bf16)d;
+    return p.u;
+}
+
+// ---------------------------------------------------------------------------------------------
+// tile table: [0] = number of row tiles; entry i at 4+4i: expert, first row, rows in tile
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restrict__ offsets, int E,
+                                                          int total_rows, int BM,
+                                                          int32_t* __restrict__ meta) {
+    __shared__ int first[kMaxE + 1];
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int e = 0; e < E; e++) {
+            const int r = offsets ? offsets[e + 1] - offsets[e] : total_rows;
+            first[e] = run;
+            run += (r + BM - 1) / BM;
+        }
+        first[E] = run;
+        meta[0] = run;
+    }
+    __syncthreads();
+    for (int e = 0; e < E; e++) {
+        const int r0 = offsets ? offsets[e] : 0;
+        const int r1 = offsets ? offsets[e + 1] : total_rows;
+        const int nt = first[e + 1] - first[e];
+        for (int i = threadIdx.x; i < nt; i += 512) {
+            int32_t* m = meta + 4 + 4 * (first[e] + i);
+            m[0] = e;
+            m[1] = r0 + i * BM;
+            m[2] = min(BM, r1 - (r0 + i * BM));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// gemm_xw
+// ---------------------------------------------------------------------------------------------
+template <int BM, int BN, int BK, int NS, bool WK, int EPI>
+__global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
+    static_assert(BN == 256, "4 wavefronts x 64 columns");
+    constexpr int TM = BM / 32;
+    constexpr int TN = 2;
+    constexpr int XBYTES = BM * BK * 2;
+    constexpr int WBYTES = BN * BK * 2;
+    constexpr int STAGE = XBYTES + WBYTES;
+    constexpr int XI = BM * BK / 8 / 256;   // direct-to-LDS loads per wavefront, X tile
+    constexpr int WI = BN * BK / 8 / 256;
+    constexpr int LPS = XI + WI;            // loads per stage per wavefront
+    constexpr int KS = BK / 16;
+    static_assert(NS >= 2 && NS <= 4, "wait-count cases below cover up to two younger stages");
+    using XT = KTile<BK>;
+    using WTK = KTile<BK>;
+    using WTN = NTile<BN>;
+
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    // ---- which tile ------------------------------------------------------------------------
+    const int n_mt = g.tile_meta[0];
+    const int G = g.group_m;
+    const int total = ((n_mt + G - 1) / G) * G * g.n_tiles_n;
+    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    const int slot = blockIdx.x / kNumXcd;
+    if (slot >= per_xcd) return;
+    const int lt = (blockIdx.x % kNumXcd) * per_xcd + slot;
+    if (lt >= total) return;
+    const int grp = lt / (G * g.n_tiles_n);
+    const int rem = lt % (G * g.n_tiles_n);
+    const int nt = rem / G;
+    const int mt = grp * G + rem % G;
+    if (mt >= n_mt) return;
+    const int expert = g.tile_meta[4 + 4 * mt];
+    const int row0 = g.tile_meta[4 + 4 * mt + 1];
+    const int rows = g.tile_meta[4 + 4 * mt + 2];
+    const int mtv = (rows + 31) >> 5;       // 32-row strips that hold rows
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const unsigned lds0 = lds_addr_of(smem);
+    const bf16* We = g.W + (long long)expert * g.w_stride;
+    const int n0 = nt * BN;                 // first column of the tile (plain epilogues)
+    const int f0 = nt * (BN / 2);           // first column per half (SWIGLU_FWD)
+
+    // ---- per-lane source pointers of the direct-to-LDS loads ----------------------------------
+    const char* xsrc[XI];
+#pragma unroll
+    for (int i = 0; i < XI; i++) {
+        const int q = (i * 4 + wave) * 64 + lane;
+        const int row = q / XT::CPR;
+        const int cc = (q % XT::CPR) ^ XT::swz(row);
+        const int grow = row0 + min(row, rows - 1);
+        xsrc[i] = reinterpret_cast<const char*>(g.X + (size_t)grow * g.ldx + cc * 8);
+    }
+    const char* wsrc[WI];
+    size_t wstep;                           // bytes per K step
+    if constexpr (WK) {
+#pragma unroll
+        for (int i = 0; i < WI; i++) {
+            const int q = (i * 4 + wave) * 64 + lane;
+            const int row = q / WTK::CPR;
+            const int cc = (q % WTK::CPR) ^ WTK::swz(row);
+            int wrow;
+            if constexpr (EPI == EPI_SWIGLU_FWD) {
+                const int half = row / (BN / 2);
+                wrow = half * g.up_rows + min(f0 + row % (BN / 2), g.N - 1);
+            } else {
+                wrow = min(n0 + row, g.N - 1);
+            }
+            wsrc[i] = reinterpret_cast<const char*>(We + (size_t)wrow * g.ldw + cc * 8);
+        }
+        wstep = (size_t)BK * 2;
+    } else {
+#pragma unroll
+        for (int i = 0; i < WI; i++) {
+            const int q = (i * 4 + wave) * 64 + lane;
+            const int krow = q / WTN::CPR;
+            const int cc = (q % WTN::CPR) ^ WTN::swz(krow);
+            const int col = min(n0 + cc * 8, g.N - 8);
+            wsrc[i] = reinterpret_cast<const char*>(We + (size_t)krow * g.ldw + col);
+        }
+        wstep = (size_t)BK * g.ldw * 2;
+    }
+
+    auto issue = [&](int kt, int stage) {
+        const unsigned sb = lds0 + stage * STAGE;
+#pragma unroll
+        for (int i = 0; i < XI; i++)
+            glds16(xsrc[i] + (size_t)kt * BK * 2, sb + ((i * 4 + wave) * 64) * 16);
+#pragma unroll
+        for (int i = 0; i < WI; i++)
+            glds16(wsrc[i] + (size_t)kt * wstep, sb + XBYTES + ((i * 4 + wave) * 64) * 16);
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; tm++)
+#pragma unroll
+        for (int tn = 0; tn < TN; tn++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[tm][tn][r] = 0.f;
+
+    // LDS rows (K-contiguous W) or columns (N-contiguous W) of this wavefront's two fragments
+    int wpos[TN];
+    if constexpr (EPI == EPI_SWIGLU_FWD) {
+        wpos[0] = wave * 32;
+        wpos[1] = BN / 2 + wave * 32;
+    } else {
+        wpos[0] = wave * 64;
+        wpos[1] = wave * 64 + 32;
+    }
+
+    const int nk = g.K / BK;
+    // ---- prologue: NS-1 stages in flight --------------------------------------------------------
+#pragma unroll
+    for (int s = 0; s < NS - 1; s++) {
+        if (s < nk) issue(s, s);
+    }
+
+    for (int kt = 0; kt < nk; kt++) {
+        // stage kt has landed once at most the loads of the younger stages are outstanding
+        const int younger = min(NS - 2, nk - 1 - kt);
+        if (younger >= NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+        else if (younger == 1) wait_vmcnt<1 * LPS>();
+        else wait_vmcnt<0>();
+        __syncthreads();
+        if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
+
+        const char* xb = smem + (kt % NS) * STAGE;
+        const char* wb = xb + XBYTES;
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {
+            bf16x8 wf[TN];
+#pragma unroll
+            for (int tn = 0; tn < TN; tn++) {
+                if constexpr (WK)
+                    wf[tn] = lds_read16(wb + WTK::off(wpos[tn] + (lane & 31), ks * 2 + (lane >> 5)));
+                else
+                    wf[tn] = WTN::frag(wb, ks, wpos[tn], lane);
+            }
+#pragma unroll
+            for (int tm = 0; tm < TM; tm++) {
+                if (tm < mtv) {
+                    const bf16x8 xf = lds_read16(xb + XT::off(tm * 32 + (lane & 31), ks * 2 + (lane >> 5)));
+#pragma unroll
+                    for (int tn = 0; tn < TN; tn++)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[tn], xf, acc[tm][tn], 0, 0, 0);
+                }
+            }
+        }
+    }
+    __syncthreads();   // every wavefront is done with the operand tiles: LDS becomes staging space
+
+    // ---- epilogue ---------------------------------------------------------------------------------
+    // acc[tm][tn][r] = C[row tm*32 + lane%32][col wpos-relative 8*(r/4) + 4*(lane/32) + r%4]
+    const int lrow = lane & 31;
+    const int lhalf = lane >> 5;
+
+    if constexpr (EPI == EPI_F32) {
+        float* out = reinterpret_cast<float*>(g.out0);
+#pragma unroll
+        for (int tm = 0; tm < TM; tm++) {
+            if (tm < mtv) {
+                const int r_in = tm * 32 + lrow;
+                if (r_in < rows) {
+                    float* orow = out + (size_t)(row0 + r_in) * g.ldo;
+#pragma unroll
+                    for (int tn = 0; tn < TN; tn++)
+#pragma unroll
+                        for (int r = 0; r < 16; r++) {
+                            const int col = n0 + wpos[tn] + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                            if (col < g.N) orow[col] = acc[tm][tn][r];
+                        }
+                }
+            }
+        }
+        return;
+    } else {
+        constexpr int SC = (EPI == EPI_SWIGLU_FWD) ? 96 : (EPI == EPI_SWIGLU_BWD ? 128 : 64);
+        constexpr int SROW = SC * 2 + 16;              // staging row stride in bytes
+        constexpr int CPRS = SC / 8;                   // 16-byte chunks per staging row
+        char* stg = smem + wave * (32 * SROW);
+#pragma unroll
+        for (int tm = 0; tm < TM; tm++) {
+            if (tm >= mtv) break;
+            const int r_in = tm * 32 + lrow;
+            // -- registers -> staging rows
+            if constexpr (EPI == EPI_STORE) {
+#pragma unroll
+                for (int tn = 0; tn < TN; tn++)
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const int c = tn * 32 + 8 * q + 4 * lhalf;
+                        *reinterpret_cast<uint2*>(stg + lrow * SROW + c * 2) =
+                            pack4(acc[tm][tn][4 * q], acc[tm][tn][4 * q + 1], acc[tm][tn][4 * q + 2],
+                                  acc[tm][tn][4 * q + 3]);
+                    }
+            } else if constexpr (EPI == EPI_SWIGLU_FWD) {
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const int c = 8 * q + 4 * lhalf;
+                    float a[4], b[4], h[4];
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        a[i] = acc[tm][0][4 * q + i];
+                        b[i] = acc[tm][1][4 * q + i];
+                        h[i] = silu_f(a[i]) * b[i];
+                    }
+                    *reinterpret_cast<uint2*>(stg + lrow * SROW + c * 2) = pack4(a[0], a[1], a[2], a[3]);
+                    *reinterpret_cast<uint2*>(stg + lrow * SROW + (32 + c) * 2) = pack4(b[0], b[1], b[2], b[3]);
+                    *reinterpret_cast<uint2*>(stg + lrow * SROW + (64 + c) * 2) = pack4(h[0], h[1], h[2], h[3]);
+                }
+            } else {   // EPI_SWIGLU_BWD
+                const bool rok = r_in < rows;
+                const size_t grow = (size_t)(row0 + (rok ? r_in : 0));
+#pragma unroll
+                for (int tn = 0; tn < TN; tn++)
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const int c = tn * 32 + 8 * q + 4 * lhalf;     // column inside the wave's 64
+                        const int col = n0 + wave * 64 + c;
+                        float da[4] = {0.f, 0.f, 0.f, 0.f}, db[4] = {0.f, 0.f, 0.f, 0.f};
+                        if (rok && col < g.N) {
+                            union { uint2 u; bf16 h[4]; } av, bv;
+                            av.u = *reinterpret_cast<const uint2*>(g.aux_a + grow * g.N + col);
+                            bv.u = *reinterpret_cast<const uint2*>(g.aux_b + grow * g.N + col);
+#pragma unroll
+                            for (int i = 0; i < 4; i++) {
+                                const float a = (float)av.h[i], b = (float)bv.h[i];
+                                const float dh = acc[tm][tn][4 * q + i];
+                                const float sg = logistic_f(a);
+                                da[i] = dh * b * sg * (1.0f + a * (1.0f - sg));
+                                db[i] = dh * a * sg;
+                            }
+                        }
+                        *reinterpret_cast<uint2*>(stg + lrow * SROW + c * 2) = pack4(da[0], da[1], da[2], da[3]);
+                        *reinterpret_cast<uint2*>(stg + lrow * SROW + (64 + c) * 2) = pack4(db[0], db[1], db[2], db[3]);
+                    }
+            }
+            // -- staging rows -> global, 16 bytes per lane
+#pragma unroll
+            for (int it = 0; it < 32 * CPRS / 64; it++) {
+                const int id = it * 64 + lane;
+                const int srow = id / CPRS;
+                const int ch = id % CPRS;
+                const int rr = tm * 32 + srow;
+                if (rr >= rows) continue;
+                const uint4 v = *reinterpret_cast<const uint4*>(stg + srow * SROW + ch * 16);
+                const size_t grow = (size_t)(row0 + rr);
+                if constexpr (EPI == EPI_STORE) {
+                    const int col = n0 + wave * 64 + ch * 8;
+                    if (col < g.N) {
+                        bf16* dst = reinterpret_cast<bf16*>(g.out0) + grow * g.ldo + col;
+                        if (g.add) {
+                            union { uint4 u; bf16 h[8]; } o, n;
+                            o.u = *reinterpret_cast<const uint4*>(dst);
+                            n.u = v;
+#pragma unroll
+                            for (int i = 0; i < 8; i++) n.h[i] = (bf16)((float)o.h[i] + (float)n.h[i]);
+                            *reinterpret_cast<uint4*>(dst) = n.u;
+                        } else {
+                            *reinterpret_cast<uint4*>(dst) = v;
+                        }
+                    }
+                } else if constexpr (EPI == EPI_SWIGLU_FWD) {
+                    const int which = ch >> 2;
+                    const int col = f0 + wave * 32 + (ch & 3) * 8;
+                    if (col < g.N) {
+                        bf16* base = reinterpret_cast<bf16*>(which == 0 ? g.out0 : (which == 1 ? g.out1 : g.out2));
+                        *reinterpret_cast<uint4*>(base + grow * g.ldo + col) = v;
+                    }
+                } else {
+                    const int which = ch >> 3;
+                    const int col = n0 + wave * 64 + (ch & 7) * 8;
+                    if (col < g.N) {
+                        bf16* dst = reinterpret_cast<bf16*>(g.out0) + grow * g.ldo + which * g.N + col;
+                        *reinterpret_cast<uint4*>(dst) = v;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// gemm_ptq: out[e][i][j] (+)= sum_l sum_{row in group e of layer l} P_l[row][i] * Q_l[row][j]
+// ---------------------------------------------------------------------------------------------
+struct PtqArgs {
+    int n_layers;
+    const void* const* P;        // device arrays of device pointers
+    const void* const* Q;
+    const int32_t* const* off;
+    int E, mdim, ndim;
+    int m_tiles, n_tiles;
+    float* out;
+    long long out_stride;        // elements between experts
+    int accumulate;
+    const void* zeros;           // >= 16 readable zero bytes
+};
+
+template <int BK, int NS>
+__global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
+    constexpr int BM = 256, BN = 256;
+    constexpr int PBYTES = BK * BM * 2;
+    constexpr int STAGE = 2 * PBYTES;
+    constexpr int PI = BK * BM / 8 / 256;     // loads per wavefront per operand per stage
+    constexpr int LPS = 2 * PI;
+    constexpr int KS = BK / 16;
+    using PT = NTile<BM>;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int per_e = g.m_tiles * g.n_tiles;
+    const int total = g.E * per_e;
+    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    const int slot = blockIdx.x / kNumXcd;
+    if (slot >= per_xcd) return;
+    const int lt = (blockIdx.x % kNumXcd) * per_xcd + slot;
+    if (lt >= total) return;
+    const int e = lt / per_e;
+    const int m0 = ((lt % per_e) / g.n_tiles) * BM;
+    const int n0 = ((lt % per_e) % g.n_tiles) * BN;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const unsigned lds0 = lds_addr_of(smem);
+
+    // number of K blocks over all layers
+    int nb = 0;
+    for (int l = 0; l < g.n_layers; l++) {
+        const int r = g.off[l][e + 1] - g.off[l][e];
+        nb += (r + BK - 1) / BK;
+    }
+    float* otile = g.out + (long long)e * g.out_stride;
+    if (nb == 0) {
+        if (!g.accumulate) {
+            for (int i = threadIdx.x; i < BM * BN; i += 256) {
+                const int r = m0 + i / BN, c = n0 + i % BN;
+                if (r < g.mdim && c < g.ndim) otile[(size_t)r * g.ndim + c] = 0.f;
+            }
+        }
+        return;
+    }
+
+    // lane geometry of the direct-to-LDS loads: slot q -> (k row, chunk)
+    int ld_krow[PI], ld_pcol[PI], ld_qcol[PI];
+#pragma unroll
+    for (int i = 0; i < PI; i++) {
+        const int q = (i * 4 + wave) * 64 + lane;
+        ld_krow[i] = q / PT::CPR;
+        const int cc = (q % PT::CPR) ^ PT::swz(ld_krow[i]);
+        ld_pcol[i] = min(m0 + cc * 8, g.mdim - 8);
+        ld_qcol[i] = min(n0 + cc * 8, g.ndim - 8);
+    }
+
+    // load cursor
+    int ld_layer = -1, ld_r = 0, ld_end = 0;
+    const bf16* ld_p = nullptr;
+    const bf16* ld_q = nullptr;
+    auto next_block = [&]() {     // advance to the next non-empty K block
+        while (ld_r >= ld_end) {
+            ld_layer++;
+            ld_r = g.off[ld_layer][e];
+            ld_end = g.off[ld_layer][e + 1];
+            ld_p = reinterpret_cast<const bf16*>(g.P[ld_layer]);
+            ld_q = reinterpret_cast<const bf16*>(g.Q[ld_layer]);
+        }
+    };
+    auto issue = [&](int stage) {
+        next_block();
+        const unsigned sb = lds0 + stage * STAGE;
+#pragma unroll
+        for (int i = 0; i < PI; i++) {
+            const int r = ld_r + ld_krow[i];
+            const bool ok = r < ld_end;
+            const void* ps = ok ? (const void*)(ld_p + (size_t)r * g.mdim + ld_pcol[i]) : g.zeros;
+            const void* qs = ok ? (const void*)(ld_q + (size_t)r * g.ndim + ld_qcol[i]) : g.zeros;
+            glds16(ps, sb + ((i * 4 + wave) * 64) * 16);
+            glds16(qs, sb + PBYTES + ((i * 4 + wave) * 64) * 16);
+        }
+        ld_r += BK;
+    };
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; a++)
+#pragma unroll
+        for (int b = 0; b < 4; b++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < NS - 1; s++)
+        if (s < nb) issue(s);
+
+    for (int kb = 0; kb < nb; kb++) {
+        const int younger = min(NS - 2, nb - 1 - kb);
+        if (younger >= NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+        else if (younger == 1) wait_vmcnt<1 * LPS>();
+        else wait_vmcnt<0>();
+        __syncthreads();
+        if (kb + NS - 1 < nb) issue((kb + NS - 1) % NS);
+
+        const char* pb = smem + (kb % NS) * STAGE;
+        const char* qb = pb + PBYTES;
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {
+            bf16x8 pf[4], qf[4];
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                pf[t] = PT::frag(pb, ks, wm * 128 + t * 32, lane);
+                qf[t] = PT::frag(qb, ks, wn * 128 + t * 32, lane);
+            }
+#pragma unroll
+            for (int a = 0; a < 4; a++)
+#pragma unroll
+                for (int b = 0; b < 4; b++)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[a], qf[b], acc[a][b], 0, 0, 0);
+        }
+    }
+
+    // acc[a][b][r] = out[i = m0 + wm*128 + a*32 + 8*(r/4) + 4*(lane/32) + r%4][j = n0 + wn*128 + b*32 + lane%32]
+#pragma unroll
+    for (int a = 0; a < 4; a++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int i = m0 + wm * 128 + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (i < g.mdim) {
+                float* orow = otile + (size_t)i * g.ndim;
+#pragma unroll
+                for (int b = 0; b < 4; b++) {
+                    const int j = n0 + wn * 128 + b * 32 + (lane & 31);
+                    if (j < g.ndim) {
+                        if (g.accumulate) orow[j] += acc[a][b][r];
+                        else orow[j] = acc[a][b][r];
+                    }
+                }
+            }
+        }
+}
+
+__global__ void chunk_offsets_kernel(int T, int chunk_rows, int nchunks, int32_t* __restrict__ off) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= nchunks) off[i] = min(T, i * chunk_rows);
+}
+
+__global__ void reduce_partials_kernel(const float* __restrict__ part, int nparts, size_t n,
+                                       float* __restrict__ out) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float v = 0.f;
+    for (int p = 0; p < nparts; p++) v += part[(size_t)p * n + i];
+    out[i] = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// launch helpers
+// ---------------------------------------------------------------------------------------------
+constexpr int kBM = 256, kBN = 256, kBK = 32, kNS = 4;
+constexpr int kGemmLds = kNS * (kBM * kBK * 2 + kBN * kBK * 2);   // 128 KiB
+
+template <bool WK, int EPI>
+hipError_t run_xw(GemmArgs a, int max_row_tiles, hipStream_t st) {
+    auto kern = gemm_xw_kernel<kBM, kBN, kBK, kNS, WK, EPI>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    a.group_m = 2;
+    const int groups = cdiv(max_row_tiles, a.group_m);
+    const int total = groups * a.group_m * a.n_tiles_n;
+    const int grid = cdiv(total, kNumXcd) * kNumXcd;
+    kern<<<grid, 256, kGemmLds, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t run_ptq(const PtqArgs& a, hipStream_t st) {
+    auto kern = gemm_ptq_kernel<kBK, kNS>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int total = a.E * a.m_tiles * a.n_tiles;
+    const int grid = cdiv(total, kNumXcd) * kNumXcd;
+    kern<<<grid, 256, kGemmLds, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t build_tiles(const int32_t* offsets, int E, int total_rows, int32_t* meta, hipStream_t st) {
+    build_tiles_kernel<<<1, 512, 0, st>>>(offsets, E, total_rows, kBM, meta);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool mfma_ffn_supported(const unipool_shape& s) {
+    return s.dtype == UNIPOOL_BF16 && s.d_model % 64 == 0 && s.d_ff % 64 == 0;
+}
+
+bool mfma_router_supported(const unipool_shape& s) {
+    return s.dtype == UNIPOOL_BF16 && s.d_model % 64 == 0 && s.E % 32 == 0;
+}
+
+hipError_t mfma_logits(const unipool_shape& s, const void* x, const void* w, float* z,
+                       int32_t* tile_meta, hipStream_t st) {
+    hipError_t e = build_tiles(nullptr, 1, s.T, tile_meta, st);
+    if (e != hipSuccess) return e;
+    GemmArgs a = {};
+    a.X = (const bf16*)x; a.ldx = s.d_model;
+    a.W = (const bf16*)w; a.w_stride = 0; a.ldw = s.d_model;
+    a.K = s.d_model; a.N = s.E; a.n_tiles_n = cdiv(s.E, kBN);
+    a.tile_meta = tile_meta; a.out0 = z; a.ldo = s.E;
+    return run_xw<true, EPI_F32>(a, cdiv(s.T, kBM), st);
+}
+
+hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
+                        const void* wgu, const void* wd, void* a_out, void* b_out, void* h_out,
+                        void* y, int32_t* tile_meta, hipStream_t st) {
+    const int S = s.T * s.k, d = s.d_model, f = s.d_ff;
+    const int max_tiles = S / kBM + s.E;
+    hipError_t e = build_tiles(offsets, s.E, S, tile_meta, st);
+    if (e != hipSuccess) return e;
+    GemmArgs a = {};
+    a.X = (const bf16*)x_perm; a.ldx = d;
+    a.W = (const bf16*)wgu; a.w_stride = 2LL * f * d; a.ldw = d;
+    a.K = d; a.N = f; a.n_tiles_n = cdiv(f, kBN / 2);
+    a.tile_meta = tile_meta; a.out0 = a_out; a.out1 = b_out; a.out2 = h_out; a.ldo = f;
+    a.up_rows = f;
+    e = run_xw<true, EPI_SWIGLU_FWD>(a, max_tiles, st);
+    if (e != hipSuccess) return e;
+    GemmArgs b = {};
+    b.X = (const bf16*)h_out; b.ldx = f;
+    b.W = (const bf16*)wd; b.w_stride = (long long)d * f; b.ldw = f;
+    b.K = f; b.N = d; b.n_tiles_n = cdiv(d, kBN);
+    b.tile_meta = tile_meta; b.out0 = y; b.ldo = d;
+    return run_xw<true, EPI_STORE>(b, max_tiles, st);
+}
+
+hipError_t mfma_ffn_dgrad(const unipool_shape& s, const void* dy, const void* a_in, const void* b_in,
+                          const int32_t* offsets, const void* wgu, const void* wd, void* dx,
+                          void* d_act, int32_t* tile_meta, hipStream_t st) {
+    const int S = s.T * s.k, d = s.d_model, f = s.d_ff;
+    const int max_tiles = S / kBM + s.E;
+    hipError_t e = build_tiles(offsets, s.E, S, tile_meta, st);
+    if (e != hipSuccess) return e;
+    GemmArgs a = {};   // dH = dY W_down (W_down[e] is [d][f]: reduction index strided), then SwiGLU backward
+    a.X = (const bf16*)dy; a.ldx = d;
+    a.W = (const bf16*)wd; a.w_stride = (long long)d * f; a.ldw = f;
+    a.K = d; a.N = f; a.n_tiles_n = cdiv(f, kBN);
+    a.tile_meta = tile_meta; a.out0 = d_act; a.ldo = 2 * f;
+    a.aux_a = (const bf16*)a_in; a.aux_b = (const bf16*)b_in;
+    e = run_xw<false, EPI_SWIGLU_BWD>(a, max_tiles, st);
+    if (e != hipSuccess) return e;
+    GemmArgs b = {};   // dX = [dA|dB] W_gate_up (W_gate_up[e] is [2f][d])
+    b.X = (const bf16*)d_act; b.ldx = 2 * f;
+    b.W = (const bf16*)wgu; b.w_stride = 2LL * f * d; b.ldw = d;
+    b.K = 2 * f; b.N = d; b.n_tiles_n = cdiv(d, kBN);
+    b.tile_meta = tile_meta; b.out0 = dx; b.ldo = d;
+    return run_xw<false, EPI_STORE>(b, max_tiles, st);
+}
+
+hipError_t mfma_ffn_wgrad(const unipool_shape& s, int n_layers, const void* const* x_perm_l,
+                          const void* const* d_act_l, const void* const* h_l,
+                          const void* const* dy_l, const int32_t* const* offsets_l,
+                          float* dwgu, float* dwd, int accumulate, const void* zeros,
+                          hipStream_t st) {
+    const int d = s.d_model, f = s.d_ff;
+    PtqArgs a = {};    // d_w_gate_up[e][n][c] = sum d_act[row][n] * x_perm[row][c]
+    a.n_layers = n_layers; a.P = d_act_l; a.Q = x_perm_l; a.off = offsets_l;
+    a.E = s.E; a.mdim = 2 * f; a.ndim = d; a.m_tiles = cdiv(2 * f, 256); a.n_tiles = cdiv(d, 256);
+    a.out = dwgu; a.out_stride = 2LL * f * d; a.accumulate = accumulate; a.zeros = zeros;
+    hipError_t e = run_ptq(a, st);
+    if (e != hipSuccess) return e;
+    PtqArgs b = {};    // d_w_down[e][c][n] = sum dy[row][c] * h[row][n]
+    b.n_layers = n_layers; b.P = dy_l; b.Q = h_l; b.off = offsets_l;
+    b.E = s.E; b.mdim = d; b.ndim = f; b.m_tiles = cdiv(d, 256); b.n_tiles = cdiv(f, 256);
+    b.out = dwd; b.out_stride = (long long)d * f; b.accumulate = accumulate; b.zeros = zeros;
+    return run_ptq(b, st);
+}
+
+hipError_t mfma_route_bwd_mm(const unipool_shape& s, const void* x, const void* w, const void* dz,
+                             float* dw, void* dx, int dx_accumulate, int32_t* tile_meta,
+                             float* wpart, const void* zeros, hipStream_t st) {
+    const int d = s.d_model, E = s.E, T = s.T;
+    // d_w_router = dz^T x: the token axis is cut into chunks whose partial products are summed in
+    // a fixed order.
+    const int nchunks = min(kRouteBwdSplit, cdiv(T, 256));
+    const int chunk_rows = cdiv(cdiv(T, nchunks), 32) * 32;
+    const int used = cdiv(T, chunk_rows);
+    // the pointer table and the chunk offsets live behind the tile table
+    int32_t* off = tile_meta;                       // [used + 1]
+    void** tab = reinterpret_cast<void**>(tile_meta + 1024);
+    chunk_offsets_kernel<<<cdiv(used + 1, 256), 256, 0, st>>>(T, chunk_rows, used, off);
+    hipError_t e = launch_set_ptrs(tab, dz, x, off, nullptr, nullptr, st);
+    if (e != hipSuccess) return e;
+    PtqArgs a = {};
+    a.n_layers = 1;
+    a.P = (const void* const*)(tab + 0); a.Q = (const void* const*)(tab + 1);
+    a.off = (const int32_t* const*)(tab + 2);
+    a.E = used; a.mdim = E; a.ndim = d; a.m_tiles = cdiv(E, 256); a.n_tiles = cdiv(d, 256);
+    a.out = wpart; a.out_stride = (long long)E * d; a.accumulate = 0; a.zeros = zeros;
+    e = run_ptq(a, st);
+    if (e != hipSuccess) return e;
+    const size_t n = (size_t)E * d;
+    reduce_partials_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(wpart, used, n, dw);
+    // dx (+)= dz W   (W is [E][d]: reduction index strided)
+    int32_t* meta2 = tile_meta + 2048;
+    e = build_tiles(nullptr, 1, T, meta2, st);
+    if (e != hipSuccess) return e;
+    GemmArgs b = {};
+    b.X = (const bf16*)dz; b.ldx = E;
+    b.W = (const bf16*)w; b.w_stride = 0; b.ldw = d;
+    b.K = E; b.N = d; b.n_tiles_n = cdiv(d, kBN);
+    b.tile_meta = meta2; b.out0 = dx; b.ldo = d; b.add = dx_accumulate;
+    return run_xw<false, EPI_STORE>(b, cdiv(T, kBM), st);
+}
+
+}  // namespace unipool

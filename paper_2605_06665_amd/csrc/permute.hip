@@ -1,0 +1,169 @@
+// Dispatch: builds the expert-contiguous row order and copies the token rows.
+//
+// The order is unique (expert-major, ascending token inside an expert), so it is computed
+// without order-dependent atomics:
+//   1. hist    : one wavefront per chunk of 64 tokens builds, in LDS, a 64-bit token mask per
+//                expert (atomic OR, order-free) and writes the per-chunk histogram;
+//   2. scan    : exclusive scan of counts -> expert_offsets; per expert, running sum over the
+//                chunks turns the histograms into per-chunk base rows;
+//   3. scatter : every chunk rebuilds its masks; the rank of a token inside its chunk is the
+//                popcount of the lower lanes' bits; row = chunk base + rank;
+//   4. copy    : one wavefront per token reads the row once and writes its k copies with
+//                16-byte accesses.
+#include "kernels.h"
+
+namespace unipool {
+
+namespace {
+
+constexpr int kChunkWaves = 4;   // chunks (wavefronts) per block
+
+__device__ __forceinline__ void build_masks(unsigned long long* mask, const int32_t* topk_idx,
+                                            int t, int T, int E, int k, int lane, int* sel) {
+    for (int e = lane; e < E; e += 64) mask[e] = 0ull;
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    if (t < T) {
+        for (int j = 0; j < k; j++) {
+            sel[j] = topk_idx[(size_t)t * k + j];
+            atomicOr(&mask[sel[j]], 1ull << lane);
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __restrict__ topk_idx,
+                                                           int T, int E, int k,
+                                                           int32_t* __restrict__ chunk_hist) {
+    extern __shared__ unsigned long long lds_mask[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int chunk = blockIdx.x * kChunkWaves + wave;
+    const int nchunks = (T + 63) / 64;
+    if (chunk >= nchunks) return;
+    unsigned long long* mask = lds_mask + (size_t)wave * E;
+    int sel[kMaxK];
+    build_masks(mask, topk_idx, chunk * 64 + lane, T, E, k, lane, sel);
+    for (int e = lane; e < E; e += 64) chunk_hist[(size_t)chunk * E + e] = __popcll(mask[e]);
+}
+
+// One block.  Thread e: offsets by a serial scan done by thread 0 (E <= 512), then the
+// running sum over chunks for expert e.
+__global__ __launch_bounds__(512) void permute_scan_kernel(const int32_t* __restrict__ counts,
+                                                           int E, int nchunks,
+                                                           int32_t* __restrict__ expert_offsets,
+                                                           int32_t* __restrict__ chunk_hist) {
+    __shared__ int off[kMaxE + 1];
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int e = 0; e < E; e++) {
+            off[e] = run;
+            run += counts[e];
+        }
+        off[E] = run;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e <= E; e += 512) expert_offsets[e] = off[e];
+    const int e = threadIdx.x;
+    if (e < E) {
+        int run = off[e];
+        for (int c = 0; c < nchunks; c++) {
+            const int h = chunk_hist[(size_t)c * E + e];
+            chunk_hist[(size_t)c * E + e] = run;
+            run += h;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void permute_scatter_kernel(
+    const int32_t* __restrict__ topk_idx, int T, int E, int k,
+    const int32_t* __restrict__ chunk_base, int32_t* __restrict__ row_of_slot,
+    int32_t* __restrict__ slot_of_row) {
+    extern __shared__ unsigned long long lds_mask[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int chunk = blockIdx.x * kChunkWaves + wave;
+    const int nchunks = (T + 63) / 64;
+    if (chunk >= nchunks) return;
+    unsigned long long* mask = lds_mask + (size_t)wave * E;
+    int sel[kMaxK];
+    const int t = chunk * 64 + lane;
+    build_masks(mask, topk_idx, t, T, E, k, lane, sel);
+    if (t < T) {
+        const unsigned long long below = (1ull << lane) - 1ull;
+        for (int j = 0; j < k; j++) {
+            const int e = sel[j];
+            const int row = chunk_base[(size_t)chunk * E + e] + __popcll(mask[e] & below);
+            row_of_slot[(size_t)t * k + j] = row;
+            slot_of_row[row] = t * k + j;
+        }
+    }
+}
+
+// One wavefront per token: 16-byte chunks of the row, read once, written k times.
+__global__ __launch_bounds__(256) void permute_copy_kernel(const uint4* __restrict__ x,
+                                                           const int32_t* __restrict__ row_of_slot,
+                                                           int T, int k, int row_chunks,
+                                                           uint4* __restrict__ x_perm) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    int rows[kMaxK];
+    for (int j = 0; j < k; j++) rows[j] = row_of_slot[(size_t)t * k + j];
+    const uint4* src = x + (size_t)t * row_chunks;
+    for (int c0 = 0; c0 < row_chunks; c0 += 256) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int c = c0 + u * 64 + lane;
+            if (c < row_chunks) v[u] = src[c];
+        }
+        for (int j = 0; j < k; j++) {
+            uint4* dst = x_perm + (size_t)rows[j] * row_chunks;
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int c = c0 + u * 64 + lane;
+                if (c < row_chunks) dst[c] = v[u];
+            }
+        }
+    }
+}
+
+// Rows whose byte length is not a multiple of 16 (only possible in float mode with odd d).
+__global__ void permute_copy_scalar_kernel(const uint32_t* __restrict__ x,
+                                           const int32_t* __restrict__ row_of_slot, int T, int k,
+                                           int row_words, uint32_t* __restrict__ x_perm) {
+    const int t = blockIdx.x;
+    for (int j = 0; j < k; j++) {
+        const int row = row_of_slot[(size_t)t * k + j];
+        for (int c = threadIdx.x; c < row_words; c += blockDim.x)
+            x_perm[(size_t)row * row_words + c] = x[(size_t)t * row_words + c];
+    }
+}
+
+}  // namespace
+
+hipError_t launch_permute(const unipool_shape& s, const void* x, const int32_t* topk_idx,
+                          const int32_t* counts, void* x_perm, int32_t* expert_offsets,
+                          int32_t* row_of_slot, int32_t* slot_of_row, int32_t* chunk_hist,
+                          hipStream_t st) {
+    const int nchunks = cdiv(s.T, 64);
+    const int nblocks = cdiv(nchunks, kChunkWaves);
+    const size_t lds = (size_t)kChunkWaves * s.E * sizeof(unsigned long long);
+    permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_idx, s.T, s.E, s.k, chunk_hist);
+    permute_scan_kernel<<<1, 512, 0, st>>>(counts, s.E, nchunks, expert_offsets, chunk_hist);
+    permute_scatter_kernel<<<nblocks, 256, lds, st>>>(topk_idx, s.T, s.E, s.k, chunk_hist,
+                                                      row_of_slot, slot_of_row);
+    const size_t row_bytes = (size_t)s.d_model * (s.dtype == UNIPOOL_BF16 ? 2 : 4);
+    if (row_bytes % 16 == 0) {
+        permute_copy_kernel<<<cdiv(s.T, 4), 256, 0, st>>>((const uint4*)x, row_of_slot, s.T, s.k,
+                                                          (int)(row_bytes / 16), (uint4*)x_perm);
+    } else {
+        permute_copy_scalar_kernel<<<s.T, 256, 0, st>>>((const uint32_t*)x, row_of_slot, s.T, s.k,
+                                                        (int)(row_bytes / 4), (uint32_t*)x_perm);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace unipool

@@ -1,0 +1,206 @@
+// NormRouter per-token kernels (paper Sec. 4.3, Eq. 7): score, top-k, gates, layer
+// statistics, and the backward of the score.  One 64-lane wavefront owns one token at a
+// time; lane j holds the logits of experts j, j+64, ... (at most 8 per lane, E <= 512).
+#include "kernels.h"
+
+namespace unipool {
+
+namespace {
+
+constexpr int kVPL = kMaxE / kWave;       // logits per lane
+constexpr int kWavesPerBlock = 4;
+constexpr int kTokPerWave = kRouterTokensPerBlock / kWavesPerBlock;
+
+// Statistics and selection for the tokens of one block.  Partial sums leave the block in a
+// fixed order, so the final reduction over blocks is deterministic.
+__global__ __launch_bounds__(256) void route_score_topk_kernel(
+    const float* __restrict__ logits, int T, int E, int k, float sigma_c, float eps,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate,
+    int32_t* __restrict__ cnt_part, float* __restrict__ psum_part) {
+    __shared__ float lds_ps[kWavesPerBlock][kMaxE];
+    __shared__ int lds_cnt[kMaxE];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < kMaxE; i += 256) lds_cnt[i] = 0;
+    __syncthreads();
+
+    float ps[kVPL];
+#pragma unroll
+    for (int i = 0; i < kVPL; i++) ps[i] = 0.f;
+
+    const int t0 = blockIdx.x * kRouterTokensPerBlock + wave * kTokPerWave;
+    for (int tt = 0; tt < kTokPerWave; tt++) {
+        const int t = t0 + tt;
+        if (t >= T) break;
+        const float* zr = logits + (size_t)t * E;
+        float z[kVPL];
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < kVPL; i++) {
+            const int e = lane + 64 * i;
+            z[i] = (e < E) ? zr[e] : 0.f;
+            ss += z[i] * z[i];
+        }
+        ss = wave_sum(ss);
+        const float scale = sigma_c / (sqrtf(ss) + eps);
+#pragma unroll
+        for (int i = 0; i < kVPL; i++) ps[i] += fmaxf(z[i], 0.f) * scale;
+
+        unsigned taken = 0;
+        for (int j = 0; j < k; j++) {
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int i = 0; i < kVPL; i++) {
+                const int e = lane + 64 * i;
+                const bool ok = (e < E) && !((taken >> i) & 1u);
+                if (ok && (z[i] > bv || bi == 0x7fffffff)) { bv = z[i]; bi = e; }
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float ov = __shfl_xor(bv, o, 64);
+                const int oi = __shfl_xor(bi, o, 64);
+                const bool other_valid = oi != 0x7fffffff;
+                const bool mine_valid = bi != 0x7fffffff;
+                const bool take = other_valid && (!mine_valid || ov > bv || (ov == bv && oi < bi));
+                if (take) { bv = ov; bi = oi; }
+            }
+            if ((bi & 63) == lane) {
+                taken |= 1u << (bi >> 6);
+                atomicAdd(&lds_cnt[bi], 1);
+                topk_idx[(size_t)t * k + j] = bi;
+                topk_gate[(size_t)t * k + j] = fmaxf(bv, 0.f) * scale;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kVPL; i++) lds_ps[wave][lane + 64 * i] = ps[i];
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += 256) {
+        float v = lds_ps[0][e];
+        v += lds_ps[1][e];
+        v += lds_ps[2][e];
+        v += lds_ps[3][e];
+        psum_part[(size_t)blockIdx.x * E + e] = v;
+        cnt_part[(size_t)blockIdx.x * E + e] = lds_cnt[e];
+    }
+}
+
+__global__ __launch_bounds__(512) void route_finalize_kernel(
+    const int32_t* __restrict__ cnt_part, const float* __restrict__ psum_part, int nblocks, int E,
+    int32_t* __restrict__ counts, float* __restrict__ psum) {
+    const int e = threadIdx.x;
+    if (e >= E) return;
+    int c = 0;
+    float p = 0.f;
+    for (int b = 0; b < nblocks; b++) {
+        c += cnt_part[(size_t)b * E + e];
+        p += psum_part[(size_t)b * E + e];
+    }
+    counts[e] = c;
+    psum[e] = p;
+}
+
+template <typename TA>
+__global__ __launch_bounds__(256) void route_bwd_dz_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ topk_idx,
+    const float* __restrict__ dgate, const float* __restrict__ aux_coef, int T, int E, int k,
+    float sigma, float c, float eps, TA* __restrict__ dz, float* __restrict__ dsigma_part) {
+    __shared__ float lds_ds[kWavesPerBlock];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    float coef[kVPL];
+#pragma unroll
+    for (int i = 0; i < kVPL; i++) {
+        const int e = lane + 64 * i;
+        coef[i] = (aux_coef != nullptr && e < E) ? aux_coef[e] : 0.f;
+    }
+    float dsig = 0.f;
+    const int t0 = blockIdx.x * kRouterTokensPerBlock + wave * kTokPerWave;
+    for (int tt = 0; tt < kTokPerWave; tt++) {
+        const int t = t0 + tt;
+        if (t >= T) break;
+        const float* zr = logits + (size_t)t * E;
+        float z[kVPL], ds[kVPL];
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < kVPL; i++) {
+            const int e = lane + 64 * i;
+            z[i] = (e < E) ? zr[e] : 0.f;
+            ss += z[i] * z[i];
+            ds[i] = coef[i];
+        }
+        ss = wave_sum(ss);
+        for (int j = 0; j < k; j++) {
+            const int sel = topk_idx[(size_t)t * k + j];
+            const float g = dgate[(size_t)t * k + j];
+#pragma unroll
+            for (int i = 0; i < kVPL; i++)
+                if (sel == lane + 64 * i) ds[i] += g;
+        }
+        const float n = sqrtf(ss);
+        const float inv = 1.0f / (n + eps);
+        float dzh[kVPL];
+        float dot = 0.f;
+#pragma unroll
+        for (int i = 0; i < kVPL; i++) {
+            const float zh = z[i] * inv;
+            dsig += ds[i] * c * fmaxf(zh, 0.f);
+            dzh[i] = (zh > 0.f) ? ds[i] * sigma * c : 0.f;
+            dot += dzh[i] * z[i];
+        }
+        dot = wave_sum(dot);
+        const float back = (n > 0.f) ? dot * inv * inv / n : 0.f;
+#pragma unroll
+        for (int i = 0; i < kVPL; i++) {
+            const int e = lane + 64 * i;
+            if (e < E) {
+                const float v = (n > 0.f) ? dzh[i] * inv - z[i] * back : 0.f;
+                dz[(size_t)t * E + e] = from_f32<TA>(v);
+            }
+        }
+    }
+    dsig = wave_sum(dsig);
+    if (lane == 0) lds_ds[wave] = dsig;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        dsigma_part[blockIdx.x] = ((lds_ds[0] + lds_ds[1]) + lds_ds[2]) + lds_ds[3];
+}
+
+__global__ void dsigma_finalize_kernel(const float* __restrict__ part, int n, float* __restrict__ out) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        float v = 0.f;
+        for (int i = 0; i < n; i++) v += part[i];
+        out[0] = v;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_route_score_topk(const unipool_shape& s, const float* logits, int32_t* topk_idx,
+                                   float* topk_gate, int32_t* counts, float* psum,
+                                   int32_t* cnt_part, float* psum_part, hipStream_t st) {
+    const int nblocks = cdiv(s.T, kRouterTokensPerBlock);
+    route_score_topk_kernel<<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps,
+                                                     topk_idx, topk_gate, cnt_part, psum_part);
+    route_finalize_kernel<<<1, 512, 0, st>>>(cnt_part, psum_part, nblocks, s.E, counts, psum);
+    return hipGetLastError();
+}
+
+hipError_t launch_route_bwd_dz(const unipool_shape& s, const float* logits, const int32_t* topk_idx,
+                               const float* dgate, const float* aux_coef, void* dz,
+                               float* dsigma_part, float* d_sigma, hipStream_t st) {
+    const int nblocks = cdiv(s.T, kRouterTokensPerBlock);
+    if (s.dtype == UNIPOOL_BF16)
+        route_bwd_dz_kernel<bf16><<<nblocks, 256, 0, st>>>(logits, topk_idx, dgate, aux_coef, s.T,
+                                                           s.E, s.k, s.sigma, s.c, s.eps,
+                                                           (bf16*)dz, dsigma_part);
+    else
+        route_bwd_dz_kernel<float><<<nblocks, 256, 0, st>>>(logits, topk_idx, dgate, aux_coef, s.T,
+                                                            s.E, s.k, s.sigma, s.c, s.eps,
+                                                            (float*)dz, dsigma_part);
+    dsigma_finalize_kernel<<<1, 64, 0, st>>>(dsigma_part, nblocks, d_sigma);
+    return hipGetLastError();
+}
+
+}  // namespace unipool

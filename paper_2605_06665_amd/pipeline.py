@@ -1,0 +1,146 @@
+"""One training step of the L layers that share an expert pool, as a sequence of C-ABI calls.
+
+Nothing here computes: it owns the device buffers (torch is the allocator) and fixes the call
+order  route -> permute -> expert_ffn_fwd -> combine  per layer,  pool_aux_loss  once, then
+combine_bwd -> expert_ffn_bwd -> combine(unit gates) -> route_bwd  per layer, and the pool
+weight gradient either inside every layer call (`wgrad="layer"`) or once at the end over all
+layers (`wgrad="pool"`, one long reduction per expert; same result)."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class LayerState:
+    topk_idx: torch.Tensor
+    topk_gate: torch.Tensor
+    logits: torch.Tensor
+    x_perm: torch.Tensor
+    offsets: torch.Tensor
+    row_of_slot: torch.Tensor
+    slot_of_row: torch.Tensor
+    act_a: torch.Tensor
+    act_b: torch.Tensor
+    act_h: torch.Tensor
+    y_perm: torch.Tensor
+    out: torch.Tensor
+    # backward
+    dy_perm: Optional[torch.Tensor] = None
+    d_act: Optional[torch.Tensor] = None
+    dx_perm: Optional[torch.Tensor] = None
+    dgate: Optional[torch.Tensor] = None
+    dx: Optional[torch.Tensor] = None
+    d_w_router: Optional[torch.Tensor] = None
+    d_sigma: Optional[torch.Tensor] = None
+
+
+class PoolStep:
+    def __init__(self, T, d_model, d_ff, E, k, L, dtype, c, eps, alpha_pool, device="cuda:0",
+                 wgrad="pool"):
+        assert wgrad in ("pool", "layer")
+        self.T, self.d, self.f, self.E, self.k, self.L = T, d_model, d_ff, E, k, L
+        self.dtype = dtype
+        self.c, self.eps, self.alpha = c, eps, alpha_pool
+        self.dev = torch.device(device)
+        self.wgrad = wgrad
+        self.act = torch.bfloat16 if dtype == B.BF16 else torch.float32
+        self.S = T * k
+        self.ws = torch.empty(B.workspace_bytes(self.shape(1.0)), dtype=torch.uint8, device=self.dev)
+        i32 = dict(dtype=torch.int32, device=self.dev)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        act = dict(dtype=self.act, device=self.dev)
+        S, f, d = self.S, d_ff, d_model
+        self.counts = torch.zeros((L, E), **i32)
+        self.psum = torch.zeros((L, E), **f32)
+        self.pool_counts = torch.zeros(E, **i32)
+        self.fbar = torch.zeros(E, **f32)
+        self.loss = torch.zeros(1, **f32)
+        self.aux_coef = torch.zeros(E, **f32)
+        self.layers: List[LayerState] = []
+        for _ in range(L):
+            st = LayerState(
+                topk_idx=torch.empty((T, k), **i32), topk_gate=torch.empty((T, k), **f32),
+                logits=torch.empty((T, E), **f32), x_perm=torch.empty((S, d), **act),
+                offsets=torch.empty(E + 1, **i32), row_of_slot=torch.empty((T, k), **i32),
+                slot_of_row=torch.empty(S, **i32), act_a=torch.empty((S, f), **act),
+                act_b=torch.empty((S, f), **act), act_h=torch.empty((S, f), **act),
+                y_perm=torch.empty((S, d), **act), out=torch.empty((T, d), **act))
+            st.dgate = torch.empty((T, k), **f32)
+            st.dx = torch.empty((T, d), **act)
+            st.d_w_router = torch.empty((E, d), **f32)
+            st.d_sigma = torch.empty(1, **f32)
+            self.layers.append(st)
+        # backward buffers: per layer when the weight gradient is deferred, shared otherwise
+        nb = L if wgrad == "pool" else 1
+        self._dy = [torch.empty((S, d), **act) for _ in range(nb)]
+        self._dact = [torch.empty((S, 2 * f), **act) for _ in range(nb)]
+        self._dxp = torch.empty((S, d), **act)
+        self.d_w_gate_up = torch.zeros((E, 2 * f, d), **f32)
+        self.d_w_down = torch.zeros((E, d, f), **f32)
+        if wgrad == "pool":
+            def tab(ts):
+                return torch.tensor([t.data_ptr() for t in ts], dtype=torch.int64, device=self.dev)
+            self._tabs = (tab([s.x_perm for s in self.layers]), tab(self._dact),
+                          tab([s.act_h for s in self.layers]), tab(self._dy),
+                          tab([s.offsets for s in self.layers]))
+
+    def shape(self, sigma: float) -> B.Shape:
+        return B.Shape(T=self.T, d_model=self.d, d_ff=self.f, E=self.E, k=self.k, L=self.L,
+                       dtype=self.dtype, sigma=float(sigma), c=self.c, eps=self.eps,
+                       alpha_pool=self.alpha)
+
+    # ------------------------------------------------------------------ forward
+    def forward_layer(self, l, x, w_router, sigma, w_gate_up, w_down):
+        st, sh, ws = self.layers[l], self.shape(sigma), self.ws
+        B.route(sh, x, w_router, st.topk_idx, st.topk_gate, st.logits, self.counts[l], self.psum[l], ws)
+        B.permute(sh, x, st.topk_idx, self.counts[l], st.x_perm, st.offsets, st.row_of_slot,
+                  st.slot_of_row, ws)
+        B.expert_ffn_fwd(sh, st.x_perm, st.offsets, w_gate_up, w_down, st.act_a, st.act_b, st.act_h,
+                         st.y_perm, ws)
+        B.combine(sh, st.y_perm, st.row_of_slot, st.topk_gate, st.out, ws)
+        return st.out
+
+    def aux_loss(self, fbar_in=None):
+        B.pool_aux_loss(self.shape(1.0), self.counts, self.psum, fbar_in, self.pool_counts, self.fbar,
+                        self.loss, self.aux_coef, self.ws)
+        return self.loss
+
+    # ------------------------------------------------------------------ backward
+    def begin_backward(self):
+        if self.wgrad == "layer":
+            self.d_w_gate_up.zero_()
+            self.d_w_down.zero_()
+
+    def backward_layer(self, l, x, w_router, sigma, w_gate_up, w_down, grad_out):
+        st, sh, ws = self.layers[l], self.shape(sigma), self.ws
+        slot = l if self.wgrad == "pool" else 0
+        dy, dact = self._dy[slot], self._dact[slot]
+        B.combine_bwd(sh, grad_out, st.y_perm, st.row_of_slot, st.topk_gate, dy, st.dgate, ws)
+        dwgu = None if self.wgrad == "pool" else self.d_w_gate_up
+        dwd = None if self.wgrad == "pool" else self.d_w_down
+        B.expert_ffn_bwd(sh, dy, st.x_perm, st.act_a, st.act_b, st.act_h, st.offsets, w_gate_up, w_down,
+                         self._dxp, dact, dwgu, dwd, ws)
+        B.combine(sh, self._dxp, st.row_of_slot, None, st.dx, ws)            # backward of the dispatch
+        B.route_bwd(sh, x, w_router, st.logits, st.topk_idx, st.dgate, self.aux_coef, st.d_w_router,
+                    st.d_sigma, st.dx, True, ws)
+        return st.dx
+
+    def end_backward(self):
+        if self.wgrad == "pool":
+            B.expert_wgrad(self.shape(1.0), self.L, *self._tabs, self.d_w_gate_up, self.d_w_down,
+                           False, self.ws)
+
+    # ------------------------------------------------------------------ whole step
+    def step(self, xs, w_routers, sigmas, w_gate_up, w_down, grad_outs, fbar_in=None):
+        for l in range(self.L):
+            self.forward_layer(l, xs[l], w_routers[l], sigmas[l], w_gate_up, w_down)
+        self.aux_loss(fbar_in)
+        self.begin_backward()
+        for l in reversed(range(self.L)):
+            self.backward_layer(l, xs[l], w_routers[l], sigmas[l], w_gate_up, w_down, grad_outs[l])
+        self.end_backward()

@@ -1,0 +1,372 @@
+"""GPU parity: every C-ABI entry point against the float64 oracle, element by element, on seeded
+inputs.  Each entry point gets the ORACLE's upstream results as its inputs (rounded to the
+activation dtype where the ABI takes activations), so one rounding-level tie in the router cannot
+shift every row downstream.  Tolerances: integers bit-exact; floats max|diff|/max|ref| <= 1e-5
+(float mode) or 1e-2 (bfloat16 mode, float accumulate)."""
+import functools
+
+import numpy as np
+import pytest
+
+from oracle import unipool_oracle as O
+from synth import workloads as W
+from tests.gpu_util import TOL, dev, host, near_tie_tokens, rel_err, round_act
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    "C1": W.WORKLOADS["C1"],
+    "f32-ragged": W.Workload("f32-ragged", L=2, E=5, d=36, f=44, k=3, T=77, dtype="f32", seed=11, c=2.0),
+    "f32-odd": W.Workload("f32-odd", L=1, E=3, d=30, f=17, k=1, T=65, dtype="f32", seed=12, c=1.7),
+    "bf16-tiles": W.Workload("bf16-tiles", L=2, E=8, d=128, f=192, k=2, T=1000, dtype="bf16", seed=13,
+                             c=2.5),
+    "bf16-skew": W.Workload("bf16-skew", L=2, E=32, d=256, f=320, k=4, T=2048, dtype="bf16", seed=14,
+                            c=2.4, skew="hot"),
+    "bf16-empty": W.Workload("bf16-empty", L=2, E=64, d=64, f=64, k=2, T=20, dtype="bf16", seed=15,
+                             c=2.65),
+    "bf16-k8": W.Workload("bf16-k8", L=1, E=512, d=128, f=64, k=8, T=300, dtype="bf16", seed=16,
+                          c=3.2, skew="zipf"),
+    "bf16-smallE": W.Workload("bf16-smallE", L=1, E=10, d=64, f=128, k=3, T=90, dtype="bf16", seed=17,
+                              c=2.0),
+}
+CASE_IDS = list(CASES)
+
+
+@functools.lru_cache(maxsize=None)
+def oracle_case(name):
+    """Inputs and the oracle's results (layer 0 in detail, whole step in `step`)."""
+    w = CASES[name]
+    xs = [W.gen_x(w, l) for l in range(w.L)]
+    wrs = [W.gen_w_router(w, l) for l in range(w.L)]
+    gs = [W.gen_grad_out(w, l) for l in range(w.L)]
+    wg, wu, wd = W.gen_pool_weights(w)
+    sigmas = [w.sigma + 0.1 * l for l in range(w.L)]
+    return dict(w=w, xs=xs, wrs=wrs, gs=gs, wg=wg, wu=wu, wd=wd, sigmas=sigmas)
+
+
+def lib():
+    import paper_2605_06665_amd as U
+    return U
+
+
+def shape_of(w, sigma=None):
+    U = lib()
+    return U.Shape(T=w.T, d_model=w.d, d_ff=w.f, E=w.E, k=w.k, L=w.L,
+                   dtype=U.BF16 if w.dtype == "bf16" else U.F32,
+                   sigma=w.sigma if sigma is None else sigma, c=w.c, eps=w.eps, alpha_pool=w.alpha)
+
+
+def workspace(sh):
+    import torch
+    return torch.empty(lib().workspace_bytes(sh), dtype=torch.uint8, device="cuda")
+
+
+def empty(shape, dtype):
+    import torch
+    dt = {"bf16": torch.bfloat16, "f32": torch.float32, "i32": torch.int32}[dtype]
+    return torch.empty(shape, dtype=dt, device="cuda")
+
+
+def pack_gate_up(wg, wu):
+    return np.concatenate([wg, wu], axis=1)          # [E, 2f, d]
+
+
+# --------------------------------------------------------------------------- router
+@pytest.mark.parametrize("name", CASE_IDS)
+def test_route(name):
+    import torch
+    c = oracle_case(name)
+    w, U = c["w"], lib()
+    sh = shape_of(w, c["sigmas"][0])
+    ref = O.route(c["xs"][0], c["wrs"][0], w.k, c["sigmas"][0], w.c, w.eps)
+    x, wr = dev(c["xs"][0], w.dtype), dev(c["wrs"][0], w.dtype)
+    idx, gate = empty((w.T, w.k), "i32"), empty((w.T, w.k), "f32")
+    logits, counts, psum = empty((w.T, w.E), "f32"), empty((w.E,), "i32"), empty((w.E,), "f32")
+    ws = workspace(sh)
+    U.route(sh, x, wr, idx, gate, logits, counts, psum, ws)
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    assert rel_err(host(logits), ref["z"]) <= tol
+    tie = near_tie_tokens(ref["z"], w.k)
+    ok = ~tie
+    gi = host(idx)
+    assert np.array_equal(gi[ok], ref["idx"][ok]), "top-k indices differ outside near-ties"
+    assert rel_err(host(gate)[ok], ref["gate"][ok]) <= tol
+    # near-tie tokens must still hold k distinct valid experts
+    assert all(len(set(r)) == w.k and 0 <= min(r) and max(r) < w.E for r in gi[tie].tolist())
+    assert np.array_equal(host(counts), np.bincount(gi.ravel(), minlength=w.E))
+    if np.array_equal(gi, ref["idx"]):
+        assert np.array_equal(host(counts), ref["counts"])
+    assert int(host(counts).sum()) == w.T * w.k
+    assert rel_err(host(psum), ref["psum"]) <= tol
+    # logits == NULL takes the workspace path and gives the same selection
+    idx2, gate2 = empty((w.T, w.k), "i32"), empty((w.T, w.k), "f32")
+    U.route(sh, x, wr, idx2, gate2, None, counts, psum, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(gate, gate2)
+
+
+# --------------------------------------------------------------------------- dispatch
+@pytest.mark.parametrize("name", CASE_IDS)
+def test_permute(name):
+    import torch
+    c = oracle_case(name)
+    w, U = c["w"], lib()
+    sh = shape_of(w)
+    r = O.route(c["xs"][0], c["wrs"][0], w.k, w.sigma, w.c, w.eps)
+    off, ros, sor = O.permutation(r["idx"], w.E)
+    x = dev(c["xs"][0], w.dtype)
+    x_perm = empty((w.S, w.d), w.dtype)
+    g_off, g_ros, g_sor = empty((w.E + 1,), "i32"), empty((w.T, w.k), "i32"), empty((w.S,), "i32")
+    U.permute(sh, x, dev(r["idx"].astype(np.int32)), dev(r["counts"].astype(np.int32)), x_perm, g_off,
+              g_ros, g_sor, workspace(sh))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(g_off), off)
+    assert np.array_equal(host(g_ros), ros)
+    assert np.array_equal(host(g_sor), sor)
+    assert np.array_equal(host(x_perm), O.permute_rows(c["xs"][0], sor, w.k))      # bitwise row copies
+
+
+# --------------------------------------------------------------------------- experts
+def _ffn_inputs(c):
+    w = c["w"]
+    r = O.route(c["xs"][0], c["wrs"][0], w.k, w.sigma, w.c, w.eps)
+    off, ros, sor = O.permutation(r["idx"], w.E)
+    x_perm = O.permute_rows(c["xs"][0], sor, w.k)
+    return r, off, ros, sor, x_perm
+
+
+@pytest.mark.parametrize("name", CASE_IDS)
+def test_expert_ffn_fwd(name):
+    import torch
+    c = oracle_case(name)
+    w, U = c["w"], lib()
+    sh = shape_of(w)
+    r, off, ros, sor, x_perm = _ffn_inputs(c)
+    a, b, h, y = O.expert_ffn_fwd(x_perm, off, c["wg"], c["wu"], c["wd"])
+    ga, gb, gh = (empty((w.S, w.f), w.dtype) for _ in range(3))
+    gy = empty((w.S, w.d), w.dtype)
+    for t in (ga, gb, gh, gy):
+        t.fill_(float("nan"))
+    U.expert_ffn_fwd(sh, dev(x_perm, w.dtype), dev(off.astype(np.int32)),
+                     dev(pack_gate_up(c["wg"], c["wu"]), w.dtype), dev(c["wd"], w.dtype), ga, gb, gh, gy,
+                     workspace(sh))
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    for got, ref_, nm in ((ga, a, "a"), (gb, b, "b"), (gh, h, "h"), (gy, y, "y")):
+        g = host(got)
+        assert np.isfinite(g).all(), nm + " has unwritten elements"
+        assert rel_err(g, ref_) <= tol, nm
+
+
+@pytest.mark.parametrize("name", CASE_IDS)
+def test_expert_ffn_bwd(name):
+    import torch
+    c = oracle_case(name)
+    w, U = c["w"], lib()
+    sh = shape_of(w)
+    r, off, ros, sor, x_perm = _ffn_inputs(c)
+    a, b, h, y = O.expert_ffn_fwd(x_perm, off, c["wg"], c["wu"], c["wd"])
+    a, b, h = round_act(a, w.dtype), round_act(b, w.dtype), round_act(h, w.dtype)   # saved activations
+    rng = np.random.default_rng(5)
+    dy = round_act(rng.standard_normal((w.S, w.d)), w.dtype)
+    dxp, dwg, dwu, dwd, da, db = O.expert_ffn_bwd(dy, x_perm, a, b, off, c["wg"], c["wu"], c["wd"])
+    # the library's d_w_down uses the saved H (rounded), the oracle recomputes it from a, b: both
+    # are within the tolerance of the exact value
+    g_dx = empty((w.S, w.d), w.dtype)
+    g_dact = empty((w.S, 2 * w.f), w.dtype)
+    g_dwgu = torch.full((w.E, 2 * w.f, w.d), 0.5, dtype=torch.float32, device="cuda")   # += semantics
+    g_dwd = torch.full((w.E, w.d, w.f), -0.25, dtype=torch.float32, device="cuda")
+    args = (dev(dy, w.dtype), dev(x_perm, w.dtype), dev(a, w.dtype), dev(b, w.dtype), dev(h, w.dtype),
+            dev(off.astype(np.int32)), dev(pack_gate_up(c["wg"], c["wu"]), w.dtype), dev(c["wd"], w.dtype))
+    ws = workspace(sh)
+    U.expert_ffn_bwd(sh, *args, g_dx, g_dact, g_dwgu, g_dwd, ws)
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    assert rel_err(host(g_dx), dxp) <= tol
+    assert rel_err(host(g_dact)[:, :w.f], da) <= tol
+    assert rel_err(host(g_dact)[:, w.f:], db) <= tol
+    assert rel_err(host(g_dwgu) - 0.5, np.concatenate([dwg, dwu], axis=1)) <= tol
+    assert rel_err(host(g_dwd) + 0.25, dwd) <= tol
+    idle = np.diff(off) == 0
+    if idle.any():      # experts without rows: gradient untouched
+        assert (host(g_dwgu)[idle] == 0.5).all() and (host(g_dwd)[idle] == -0.25).all()
+    # dgrad only (NULL weight gradients) gives the same dx / d_act
+    g_dx2, g_dact2 = torch.empty_like(g_dx), torch.empty_like(g_dact)
+    U.expert_ffn_bwd(sh, *args, g_dx2, g_dact2, None, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(g_dx, g_dx2) and torch.equal(g_dact, g_dact2)
+
+
+# --------------------------------------------------------------------------- combine
+@pytest.mark.parametrize("name", CASE_IDS)
+def test_combine_and_bwd(name):
+    import torch
+    c = oracle_case(name)
+    w, U = c["w"], lib()
+    sh = shape_of(w)
+    r, off, ros, sor, x_perm = _ffn_inputs(c)
+    rng = np.random.default_rng(6)
+    y = round_act(rng.standard_normal((w.S, w.d)), w.dtype)
+    gate = r["gate"].astype(np.float32)
+    out = O.combine(y, ros, gate)
+    out1 = O.combine(y, ros, None)
+    g_out = empty((w.T, w.d), w.dtype)
+    d_ros = dev(ros.astype(np.int32))
+    U.combine(sh, dev(y, w.dtype), d_ros, dev(gate), g_out)
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    assert rel_err(host(g_out), out) <= tol
+    U.combine(sh, dev(y, w.dtype), d_ros, None, g_out)
+    torch.cuda.synchronize()
+    assert rel_err(host(g_out), out1) <= tol
+    dout = round_act(rng.standard_normal((w.T, w.d)), w.dtype)
+    dy, dgate = O.combine_bwd(dout, y, ros, gate)
+    g_dy, g_dg = empty((w.S, w.d), w.dtype), empty((w.T, w.k), "f32")
+    U.combine_bwd(sh, dev(dout, w.dtype), dev(y, w.dtype), d_ros, dev(gate), g_dy, g_dg)
+    torch.cuda.synchronize()
+    assert rel_err(host(g_dy), dy) <= tol
+    assert rel_err(host(g_dg), dgate) <= max(tol, 1e-5)
+
+
+# --------------------------------------------------------------------------- pool loss
+@pytest.mark.parametrize("name", CASE_IDS)
+@pytest.mark.parametrize("lagged", [False, True])
+def test_pool_aux_loss(name, lagged):
+    import torch
+    c = oracle_case(name)
+    w, U = c["w"], lib()
+    sh = shape_of(w)
+    rs = [O.route(c["xs"][l], c["wrs"][l], w.k, c["sigmas"][l], w.c, w.eps) for l in range(w.L)]
+    counts = np.stack([r["counts"] for r in rs])
+    psum = np.stack([r["psum"] for r in rs])
+    fin = None
+    if lagged:
+        fin = np.random.default_rng(3).random(w.E).astype(np.float32)
+        fin /= fin.sum()
+    pc, fbar, loss, coef = O.pool_aux_loss(counts, psum.astype(np.float32), w.T, w.k, w.alpha, fin)
+    g_pc, g_fb, g_loss, g_coef = empty((w.E,), "i32"), empty((w.E,), "f32"), empty((1,), "f32"), empty((w.E,), "f32")
+    U.pool_aux_loss(sh, dev(counts.astype(np.int32)), dev(psum.astype(np.float32)),
+                    None if fin is None else dev(fin), g_pc, g_fb, g_loss, g_coef)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(g_pc), pc)
+    assert rel_err(host(g_fb), fbar) <= 1e-6
+    assert abs(float(host(g_loss)[0]) - loss) <= 1e-5 * abs(loss)
+    assert rel_err(host(g_coef), coef) <= 1e-6
+    assert int(host(g_pc).sum()) == w.L * w.T * w.k
+
+
+# --------------------------------------------------------------------------- router backward
+@pytest.mark.parametrize("name", CASE_IDS)
+@pytest.mark.parametrize("with_aux", [True, False])
+def test_route_bwd(name, with_aux):
+    import torch
+    c = oracle_case(name)
+    w, U = c["w"], lib()
+    sigma = c["sigmas"][0]
+    sh = shape_of(w, sigma)
+    r = O.route(c["xs"][0], c["wrs"][0], w.k, sigma, w.c, w.eps)
+    rng = np.random.default_rng(7)
+    dgate = rng.standard_normal((w.T, w.k)).astype(np.float32)
+    coef = (rng.random(w.E) * 1e-3).astype(np.float32) if with_aux else None
+    z32 = r["z"].astype(np.float32)                     # the saved logits are float
+    dx, dw, dsig, dz = O.route_bwd(c["xs"][0], c["wrs"][0], z32, r["idx"], dgate, coef, sigma, w.c, w.eps)
+    base = round_act(rng.standard_normal((w.T, w.d)), w.dtype)
+    g_dx = dev(base, w.dtype)
+    g_dw, g_ds = empty((w.E, w.d), "f32"), empty((1,), "f32")
+    ws = workspace(sh)
+    args = (dev(c["xs"][0], w.dtype), dev(c["wrs"][0], w.dtype), dev(z32), dev(r["idx"].astype(np.int32)),
+            dev(dgate), None if coef is None else dev(coef))
+    U.route_bwd(sh, *args, g_dw, g_ds, g_dx, True, ws)
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    assert rel_err(host(g_dw), dw) <= tol
+    assert abs(float(host(g_ds)[0]) - dsig) <= tol * max(abs(dsig), 1e-3)
+    assert rel_err(host(g_dx), base.astype(np.float64) + dx) <= tol
+    g_dx2 = empty((w.T, w.d), w.dtype)
+    U.route_bwd(sh, *args, g_dw, g_ds, g_dx2, False, ws)
+    torch.cuda.synchronize()
+    # dx alone is small next to the N(0,1) base above: check it on its own scale too
+    assert rel_err(host(g_dx2), dx) <= tol
+
+
+# --------------------------------------------------------------------------- whole step
+@pytest.mark.parametrize("name", CASE_IDS)
+@pytest.mark.parametrize("wgrad", ["pool", "layer"])
+def test_whole_step(name, wgrad):
+    import torch
+    from paper_2605_06665_amd.pipeline import PoolStep
+    c = oracle_case(name)
+    w, U = c["w"], lib()
+    ps = PoolStep(w.T, w.d, w.f, w.E, w.k, w.L, U.BF16 if w.dtype == "bf16" else U.F32, w.c, w.eps,
+                  w.alpha, wgrad=wgrad)
+    xs = [dev(x, w.dtype) for x in c["xs"]]
+    wrs = [dev(x, w.dtype) for x in c["wrs"]]
+    gs = [dev(x, w.dtype) for x in c["gs"]]
+    wgu, wd = dev(pack_gate_up(c["wg"], c["wu"]), w.dtype), dev(c["wd"], w.dtype)
+    ps.step(xs, wrs, c["sigmas"], wgu, wd, gs)
+    torch.cuda.synchronize()
+    # impose the GPU's selection on near-tie tokens only; everywhere else it must equal the oracle's
+    idxs = []
+    n_tie = 0
+    for l in range(w.L):
+        z = O.router_logits(c["xs"][l], c["wrs"][l])
+        ref_idx = O.topk_select(z, w.k)
+        gi = host(ps.layers[l].topk_idx)
+        tie = near_tie_tokens(z, w.k)
+        assert np.array_equal(gi[~tie], ref_idx[~tie])
+        n_tie += int(tie.sum())
+        ref_idx[tie] = gi[tie]
+        idxs.append(ref_idx)
+    ref = O.pool_step(c["xs"], c["wrs"], c["wg"], c["wu"], c["wd"], c["gs"], w.k, c["sigmas"], w.c, w.eps,
+                      w.alpha, idxs=idxs)
+    tol = TOL[w.dtype]
+    # end to end the chain rounds to the activation dtype at every hand-over; the bar stays the same
+    tol2 = tol
+    assert np.array_equal(host(ps.counts), ref["counts"])
+    assert np.array_equal(host(ps.pool_counts), ref["pool_counts"])
+    assert abs(float(host(ps.loss)[0]) - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+    for l in range(w.L):
+        st, fw, bw = ps.layers[l], ref["fw"][l], ref["bw"][l]
+        assert np.array_equal(host(st.row_of_slot), fw["row_of_slot"])
+        assert rel_err(host(st.out), fw["out"]) <= tol2, "out"
+        assert rel_err(host(st.dx), bw["dx"]) <= tol2, "dx"
+        assert rel_err(host(st.d_w_router), bw["dw_router"]) <= tol2, "dw_router"
+        assert abs(float(host(st.d_sigma)[0]) - bw["dsigma"]) <= tol2 * max(abs(bw["dsigma"]), 1e-3)
+    assert rel_err(host(ps.d_w_gate_up), np.concatenate([ref["dw_gate"], ref["dw_up"]], axis=1)) <= tol2
+    assert rel_err(host(ps.d_w_down), ref["dw_down"]) <= tol2
+    # determinism: a second step gives bitwise the same results
+    keep = [ps.d_w_gate_up.clone(), ps.d_w_down.clone(), ps.layers[0].dx.clone(), ps.layers[0].out.clone(),
+            ps.loss.clone()]
+    ps.step(xs, wrs, c["sigmas"], wgu, wd, gs)
+    torch.cuda.synchronize()
+    again = [ps.d_w_gate_up, ps.d_w_down, ps.layers[0].dx, ps.layers[0].out, ps.loss]
+    assert all(torch.equal(a, b) for a, b in zip(keep, again))
+
+
+# --------------------------------------------------------------------------- argument checks
+def test_invalid_arguments_are_rejected_before_launch():
+    import torch
+    U = lib()
+    w = CASES["C1"]
+    sh = shape_of(w)
+    ws = workspace(sh)
+    x = empty((w.T, w.d), "f32")
+    with pytest.raises(U.UniPoolError, match="NULL"):
+        U.route(sh, x, None, None, None, None, None, None, ws)
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(U.UniPoolError, match="workspace"):
+        U.permute(sh, x, x, x, x, x, x, x, small)
+    bad = shape_of(w)
+    bad.k = 9
+    with pytest.raises(U.UniPoolError, match="k=9"):
+        U.combine(bad, x, x, None, x)
+    bad = shape_of(CASES["bf16-tiles"])
+    bad.d_model = 100
+    with pytest.raises(U.UniPoolError, match="multiples of 64"):
+        U.combine(bad, x, x, None, x)
+    bad = shape_of(w)
+    bad.sigma = 0.0
+    with pytest.raises(U.UniPoolError, match="sigma"):
+        U.combine(bad, x, x, None, x)
+    torch.cuda.synchronize()
