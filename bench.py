@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Benchmark of the shared-pool MoE layer, forward + backward, on one MI355X.
+
+One step = forward of all L layers that share the pool (route, permute, expert FFN, combine),
+the pool auxiliary loss, and the backward of all L layers (combine-bwd, expert dgrad, dispatch-bwd,
+router-bwd) with the pool weight gradient.  Inputs are synthetic, drawn on the device before the
+timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--wgrad pool|layer]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C5")
+    ap.add_argument("--wgrad", default="pool", choices=["pool", "layer"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--oracle-tokens", type=int, default=512)
+    return ap.parse_args()
+
+
+def cpu_baseline(w, xs0, wr0, g0, wg, wu, wd, n_tok):
+    """The oracle as it stands, timed on the host: one layer, the first n_tok tokens, fwd + bwd."""
+    import numpy as np
+    from oracle import unipool_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    x = xs0[:n_tok].float().cpu().numpy()
+    g = g0[:n_tok].float().cpu().numpy()
+    wr = wr0.float().cpu().numpy()
+    wg_h, wu_h, wd_h = (t.float().cpu().numpy() for t in (wg, wu, wd))
+    t0 = time.perf_counter()
+    fw = O.moe_layer_fwd(x, wr, wg_h, wu_h, wd_h, w.k, w.sigma, w.c, w.eps)
+    _, _, _, coef = O.pool_aux_loss(fw["counts"][None], fw["psum"][None], n_tok, w.k, w.alpha)
+    O.moe_layer_bwd(fw, x, wr, wg_h, wu_h, wd_h, g, coef, w.k, w.sigma, w.c, w.eps)
+    dt = time.perf_counter() - t0
+    return {"value": n_tok / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "one layer, first %d tokens of %s, fwd+bwd in float64 numpy, %.1f s; work is linear "
+                      "in tokens at fixed shape" % (n_tok, w.name, dt)}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import __graft_entry__ as entry
+    entry.ensure_built()
+    import paper_2605_06665_amd as U
+    from paper_2605_06665_amd.pipeline import PoolStep
+    from synth import workloads as W
+
+    w = W.WORKLOADS[a.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    dtype = U.BF16 if w.dtype == "bf16" else U.F32
+    xs = [W.gen_x_torch(w, l, dev) for l in range(w.L)]
+    wrs = [W.gen_w_router_torch(w, l, dev) for l in range(w.L)]
+    gs = [W.gen_grad_out_torch(w, l, dev) for l in range(w.L)]
+    wg, wu, wd = W.gen_pool_weights_torch(w, dev)
+    wgu = torch.cat([wg, wu], dim=1).contiguous()
+    sigmas = [w.sigma] * w.L
+    ps = PoolStep(w.T, w.d, w.f, w.E, w.k, w.L, dtype, w.c, w.eps, w.alpha, device=dev, wgrad=a.wgrad)
+    torch.cuda.synchronize()
+
+    for _ in range(a.warmup):
+        ps.step(xs, wrs, sigmas, wgu, wd, gs)
+    torch.cuda.synchronize()
+    ps.timing = True                      # HIP events around the GEMM entry points, on the launch stream
+    ps.events = []
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        ps.step(xs, wrs, sigmas, wgu, wd, gs)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt / a.steps * 1e3
+
+    # ---- per-entry-point device times over the timed region
+    agg = {}
+    for name, e0, e1 in ps.events:
+        agg.setdefault(name, []).append(e0.elapsed_time(e1))
+    S = w.S
+    gemm_flops_third = 6.0 * S * w.d * w.f            # one of fwd / dgrad / wgrad, per layer
+    n_xw = 4 * w.L * a.steps                          # gate-up, down, dH, dX launches
+    t_xw_ms = sum(agg.get("expert_ffn_fwd", [])) + sum(agg.get("expert_ffn_bwd", []))
+    xw_flops_per_launch = 2.0 * gemm_flops_third / 4.0
+    avg_xw_ms = t_xw_ms / n_xw
+    xw_tflops = xw_flops_per_launch / (avg_xw_ms * 1e-3) / 1e12
+    t_wg_ms = sum(agg.get("expert_wgrad", []))
+    all_gemm_tflops = 3.0 * gemm_flops_third * w.L * a.steps / ((t_xw_ms + t_wg_ms) * 1e-3) / 1e12 \
+        if a.wgrad == "pool" else 3.0 * gemm_flops_third * w.L * a.steps / (t_xw_ms * 1e-3) / 1e12
+    act_b = 2 if w.dtype == "bf16" else 4
+
+    def hbm(name, nbytes, calls_per_step):
+        ts = agg.get(name, [])
+        if not ts:
+            return None
+        avg = sum(ts) / len(ts)
+        return {"GB/s": nbytes / (avg * 1e-3) / 1e9, "frac": nbytes / (avg * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                "avg_ms": avg, "algorithmic_bytes": nbytes}
+    others = {
+        "grouped_gemm_all": {"TFLOP/s": all_gemm_tflops, "frac": all_gemm_tflops / PEAK_BF16_TFLOPS,
+                             "wgrad": a.wgrad, "gemm_ms_per_step": (t_xw_ms + t_wg_ms) / a.steps},
+        "route": hbm("route", act_b * w.T * w.d + 4 * w.T * w.E + 8 * w.T * w.k, w.L),
+        "permute": hbm("permute", act_b * w.T * w.d + act_b * S * w.d + 12 * S, w.L),
+        "combine": hbm("combine", act_b * S * w.d + act_b * w.T * w.d + 8 * S, w.L),
+        "combine_bwd": hbm("combine_bwd", act_b * w.T * w.d + 2 * act_b * S * w.d + 12 * S, w.L),
+    }
+    if a.wgrad == "pool" and t_wg_ms > 0:
+        wg_tflops = gemm_flops_third * w.L * a.steps / (t_wg_ms * 1e-3) / 1e12
+        others["wgrad_pool"] = {"TFLOP/s": wg_tflops, "frac": wg_tflops / PEAK_BF16_TFLOPS}
+
+    out = {
+        "metric": "shared-pool MoE layer fwd+bwd tokens/s; grouped-GEMM % bf16 MFMA peak",
+        "value": w.L * w.T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "L": w.L, "E": w.E, "d_model": w.d, "d_ff": w.f, "top_k": w.k,
+                   "tokens_per_layer": w.T, "skew": w.skew, "wgrad": a.wgrad,
+                   "tokens_counted": "L*T token-layer evaluations per step"},
+        "roofline": {"bound": "mfma", "achieved": xw_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": xw_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "gemm_xw (grouped bf16 GEMM: gate-up, down, dH, dX)",
+                     "avg_launch_ms": avg_xw_ms, "launches": n_xw,
+                     "flops_per_launch": xw_flops_per_launch},
+        "roofline_others": others,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, xs[0], wrs[0], gs[0], wg, wu, wd, a.oracle_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

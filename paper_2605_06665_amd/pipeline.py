@@ -48,6 +48,8 @@ class PoolStep:
         self.c, self.eps, self.alpha = c, eps, alpha_pool
         self.dev = torch.device(device)
         self.wgrad = wgrad
+        self.timing = False          # when set, HIP events bracket every entry point on its stream
+        self.events = []             # (entry point, start event, end event)
         self.act = torch.bfloat16 if dtype == B.BF16 else torch.float32
         self.S = T * k
         self.ws = torch.empty(B.workspace_bytes(self.shape(1.0)), dtype=torch.uint8, device=self.dev)
@@ -94,19 +96,29 @@ class PoolStep:
                        dtype=self.dtype, sigma=float(sigma), c=self.c, eps=self.eps,
                        alpha_pool=self.alpha)
 
+    def _call(self, fn, *args):
+        if not self.timing:
+            return fn(*args)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()                  # torch's current stream is the one the binding launches on
+        fn(*args)
+        e1.record()
+        self.events.append((fn.__name__, e0, e1))
+
     # ------------------------------------------------------------------ forward
     def forward_layer(self, l, x, w_router, sigma, w_gate_up, w_down):
         st, sh, ws = self.layers[l], self.shape(sigma), self.ws
-        B.route(sh, x, w_router, st.topk_idx, st.topk_gate, st.logits, self.counts[l], self.psum[l], ws)
-        B.permute(sh, x, st.topk_idx, self.counts[l], st.x_perm, st.offsets, st.row_of_slot,
+        self._call(B.route, sh, x, w_router, st.topk_idx, st.topk_gate, st.logits, self.counts[l], self.psum[l], ws)
+        self._call(B.permute, sh, x, st.topk_idx, self.counts[l], st.x_perm, st.offsets, st.row_of_slot,
                   st.slot_of_row, ws)
-        B.expert_ffn_fwd(sh, st.x_perm, st.offsets, w_gate_up, w_down, st.act_a, st.act_b, st.act_h,
+        self._call(B.expert_ffn_fwd, sh, st.x_perm, st.offsets, w_gate_up, w_down, st.act_a, st.act_b, st.act_h,
                          st.y_perm, ws)
-        B.combine(sh, st.y_perm, st.row_of_slot, st.topk_gate, st.out, ws)
+        self._call(B.combine, sh, st.y_perm, st.row_of_slot, st.topk_gate, st.out, ws)
         return st.out
 
     def aux_loss(self, fbar_in=None):
-        B.pool_aux_loss(self.shape(1.0), self.counts, self.psum, fbar_in, self.pool_counts, self.fbar,
+        self._call(B.pool_aux_loss, self.shape(1.0), self.counts, self.psum, fbar_in, self.pool_counts, self.fbar,
                         self.loss, self.aux_coef, self.ws)
         return self.loss
 
@@ -120,19 +132,19 @@ class PoolStep:
         st, sh, ws = self.layers[l], self.shape(sigma), self.ws
         slot = l if self.wgrad == "pool" else 0
         dy, dact = self._dy[slot], self._dact[slot]
-        B.combine_bwd(sh, grad_out, st.y_perm, st.row_of_slot, st.topk_gate, dy, st.dgate, ws)
+        self._call(B.combine_bwd, sh, grad_out, st.y_perm, st.row_of_slot, st.topk_gate, dy, st.dgate, ws)
         dwgu = None if self.wgrad == "pool" else self.d_w_gate_up
         dwd = None if self.wgrad == "pool" else self.d_w_down
-        B.expert_ffn_bwd(sh, dy, st.x_perm, st.act_a, st.act_b, st.act_h, st.offsets, w_gate_up, w_down,
+        self._call(B.expert_ffn_bwd, sh, dy, st.x_perm, st.act_a, st.act_b, st.act_h, st.offsets, w_gate_up, w_down,
                          self._dxp, dact, dwgu, dwd, ws)
-        B.combine(sh, self._dxp, st.row_of_slot, None, st.dx, ws)            # backward of the dispatch
-        B.route_bwd(sh, x, w_router, st.logits, st.topk_idx, st.dgate, self.aux_coef, st.d_w_router,
+        self._call(B.combine, sh, self._dxp, st.row_of_slot, None, st.dx, ws)            # backward of the dispatch
+        self._call(B.route_bwd, sh, x, w_router, st.logits, st.topk_idx, st.dgate, self.aux_coef, st.d_w_router,
                     st.d_sigma, st.dx, True, ws)
         return st.dx
 
     def end_backward(self):
         if self.wgrad == "pool":
-            B.expert_wgrad(self.shape(1.0), self.L, *self._tabs, self.d_w_gate_up, self.d_w_down,
+            self._call(B.expert_wgrad, self.shape(1.0), self.L, *self._tabs, self.d_w_gate_up, self.d_w_down,
                            False, self.ws)
 
     # ------------------------------------------------------------------ whole step
