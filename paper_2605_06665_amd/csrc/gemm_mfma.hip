@@ -22,6 +22,8 @@
 //   * Row groups come from a device-side tile table; nothing is read back to the host.  Tiles are
 //     walked in an order that keeps the tiles of one expert on one XCD (workgroup ids are dealt
 //     round-robin to the 8 XCDs, each of which has its own L2).
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace unipool {
@@ -160,10 +162,13 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
 // ---------------------------------------------------------------------------------------------
 // gemm_xw
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int NS, bool WK, int EPI>
-__global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
-    static_assert(BN == 256, "4 wavefronts x 64 columns");
-    constexpr int TM = BM / 32;
+// One 256 x 256 output tile.  The four wavefronts split the columns (64 each) and all own every
+// 32-row strip, so a tile with few rows skips whole strips in all of them alike.  MTV = number
+// of strips that hold rows; the body is instantiated per MTV so that the K loop is straight-line
+// code and the accumulators of absent strips do not exist.
+template <int BM, int BN, int BK, int NS, bool WK, int EPI, int MTV>
+__device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int expert, int row0, int rows,
+                                        int nt) {
     constexpr int TN = 2;
     constexpr int XBYTES = BM * BK * 2;
     constexpr int WBYTES = BN * BK * 2;
@@ -172,40 +177,28 @@ __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
     constexpr int WI = BN * BK / 8 / 256;
     constexpr int LPS = XI + WI;            // loads per stage per wavefront
     constexpr int KS = BK / 16;
-    static_assert(NS >= 2 && NS <= 4, "wait-count cases below cover up to two younger stages");
+    static_assert(KS % 2 == 0 && NS == 4, "fragment buffer parity and wait counts assume this");
     using XT = KTile<BK>;
     using WTK = KTile<BK>;
     using WTN = NTile<BN>;
+    using std::integral_constant;
 
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
-
-    // ---- which tile ------------------------------------------------------------------------
-    const int n_mt = g.tile_meta[0];
-    const int G = g.group_m;
-    const int total = ((n_mt + G - 1) / G) * G * g.n_tiles_n;
-    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
-    const int slot = blockIdx.x / kNumXcd;
-    if (slot >= per_xcd) return;
-    const int lt = (blockIdx.x % kNumXcd) * per_xcd + slot;
-    if (lt >= total) return;
-    const int grp = lt / (G * g.n_tiles_n);
-    const int rem = lt % (G * g.n_tiles_n);
-    const int nt = rem / G;
-    const int mt = grp * G + rem % G;
-    if (mt >= n_mt) return;
-    const int expert = g.tile_meta[4 + 4 * mt];
-    const int row0 = g.tile_meta[4 + 4 * mt + 1];
-    const int rows = g.tile_meta[4 + 4 * mt + 2];
-    const int mtv = (rows + 31) >> 5;       // 32-row strips that hold rows
-
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    // The per-MTV bodies are alternatives of one switch.  Their set-up code is identical, and if
+    // the compiler merges it in front of the switch the merged values stay live across all eight
+    // bodies and spill; spill code is scratch traffic, whose wait counts would then serialise the
+    // direct-to-LDS pipeline.  Making the inputs opaque here keeps every body self-contained.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    asm volatile("" : "+s"(expert), "+s"(row0), "+s"(rows), "+s"(nt));
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
     const unsigned lds0 = lds_addr_of(smem);
     const bf16* We = g.W + (long long)expert * g.w_stride;
     const int n0 = nt * BN;                 // first column of the tile (plain epilogues)
     const int f0 = nt * (BN / 2);           // first column per half (SWIGLU_FWD)
 
     // ---- per-lane source pointers of the direct-to-LDS loads ----------------------------------
+    // (rows of absent strips are loaded too, from the last valid row: they are never multiplied)
     const char* xsrc[XI];
 #pragma unroll
     for (int i = 0; i < XI; i++) {
@@ -255,9 +248,9 @@ __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
             glds16(wsrc[i] + (size_t)kt * wstep, sb + XBYTES + ((i * 4 + wave) * 64) * 16);
     };
 
-    f32x16 acc[TM][TN];
+    f32x16 acc[MTV][TN];
 #pragma unroll
-    for (int tm = 0; tm < TM; tm++)
+    for (int tm = 0; tm < MTV; tm++)
 #pragma unroll
         for (int tn = 0; tn < TN; tn++)
 #pragma unroll
@@ -274,42 +267,65 @@ __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
     }
 
     const int nk = g.K / BK;
-    // ---- prologue: NS-1 stages in flight --------------------------------------------------------
-#pragma unroll
-    for (int s = 0; s < NS - 1; s++) {
-        if (s < nk) issue(s, s);
-    }
-
-    for (int kt = 0; kt < nk; kt++) {
-        // stage kt has landed once at most the loads of the younger stages are outstanding
-        const int younger = min(NS - 2, nk - 1 - kt);
-        if (younger >= NS - 2) wait_vmcnt<(NS - 2) * LPS>();
-        else if (younger == 1) wait_vmcnt<1 * LPS>();
-        else wait_vmcnt<0>();
-        __syncthreads();
-        if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
-
-        const char* xb = smem + (kt % NS) * STAGE;
+    // ---- software pipeline ----------------------------------------------------------------------
+    // Stages kt+1 .. kt+NS-2 are in flight while stage kt is multiplied.  Fragments are double
+    // buffered in registers: while the MFMAs of one 16-wide K slice run, the fragments of the next
+    // slice (or of the first slice of the next stage) are fetched from LDS.
+    bf16x8 wfr[2][TN], xfr[2][MTV];
+    auto load_frags = [&](int stage, int ks, int buf) {
+        const char* xb = smem + stage * STAGE;
         const char* wb = xb + XBYTES;
 #pragma unroll
+        for (int tn = 0; tn < TN; tn++) {
+            if constexpr (WK)
+                wfr[buf][tn] = lds_read16(wb + WTK::off(wpos[tn] + (lane & 31), ks * 2 + (lane >> 5)));
+            else
+                wfr[buf][tn] = WTN::frag(wb, ks, wpos[tn], lane);
+        }
+#pragma unroll
+        for (int tm = 0; tm < MTV; tm++)
+            xfr[buf][tm] = lds_read16(xb + XT::off(tm * 32 + (lane & 31), ks * 2 + (lane >> 5)));
+    };
+    auto mfmas = [&](int buf) {
+#pragma unroll
+        for (int tm = 0; tm < MTV; tm++)
+#pragma unroll
+            for (int tn = 0; tn < TN; tn++)
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[buf][tn], xfr[buf][tm],
+                                                                      acc[tm][tn], 0, 0, 0);
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; s++)
+        if (s < nk) issue(s, s);
+    {
+        const int y0 = min(NS - 2, nk - 1);
+        if (y0 >= 2) wait_vmcnt<2 * LPS>();
+        else if (y0 == 1) wait_vmcnt<1 * LPS>();
+        else wait_vmcnt<0>();
+    }
+    __syncthreads();
+    load_frags(0, 0, 0);
+    // One loop, one copy of the MFMA code (a second copy for the tail makes the register allocator
+    // move the accumulators between register files).  The sched_barriers keep the LDS reads of
+    // the next slice ahead of this slice's MFMAs: the scheduler would otherwise sink them next to
+    // their consumers and expose the LDS latency.
+    for (int kt = 0; kt < nk; kt++) {
+        const int stage = kt % NS;
+#pragma unroll
         for (int ks = 0; ks < KS; ks++) {
-            bf16x8 wf[TN];
-#pragma unroll
-            for (int tn = 0; tn < TN; tn++) {
-                if constexpr (WK)
-                    wf[tn] = lds_read16(wb + WTK::off(wpos[tn] + (lane & 31), ks * 2 + (lane >> 5)));
-                else
-                    wf[tn] = WTN::frag(wb, ks, wpos[tn], lane);
+            if (ks + 1 < KS) {
+                load_frags(stage, ks + 1, (ks + 1) & 1);
+            } else {
+                // stage kt+1 must have landed; at most stage kt+2 may still be in flight
+                if (nk - 1 - kt >= 2) wait_vmcnt<(NS - 3) * LPS>();
+                else wait_vmcnt<0>();
+                __syncthreads();      // stage kt+1 is visible; every wavefront has left stage kt-1
+                if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
+                load_frags((kt + 1) % NS, 0, 0);      // after the last stage: unused, in bounds
             }
-#pragma unroll
-            for (int tm = 0; tm < TM; tm++) {
-                if (tm < mtv) {
-                    const bf16x8 xf = lds_read16(xb + XT::off(tm * 32 + (lane & 31), ks * 2 + (lane >> 5)));
-#pragma unroll
-                    for (int tn = 0; tn < TN; tn++)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[tn], xf, acc[tm][tn], 0, 0, 0);
-                }
-            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(ks & 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     __syncthreads();   // every wavefront is done with the operand tiles: LDS becomes staging space
@@ -322,30 +338,26 @@ __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
     if constexpr (EPI == EPI_F32) {
         float* out = reinterpret_cast<float*>(g.out0);
 #pragma unroll
-        for (int tm = 0; tm < TM; tm++) {
-            if (tm < mtv) {
-                const int r_in = tm * 32 + lrow;
-                if (r_in < rows) {
-                    float* orow = out + (size_t)(row0 + r_in) * g.ldo;
+        for (int tm = 0; tm < MTV; tm++) {
+            const int r_in = tm * 32 + lrow;
+            if (r_in < rows) {
+                float* orow = out + (size_t)(row0 + r_in) * g.ldo;
 #pragma unroll
-                    for (int tn = 0; tn < TN; tn++)
+                for (int tn = 0; tn < TN; tn++)
 #pragma unroll
-                        for (int r = 0; r < 16; r++) {
-                            const int col = n0 + wpos[tn] + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-                            if (col < g.N) orow[col] = acc[tm][tn][r];
-                        }
-                }
+                    for (int r = 0; r < 16; r++) {
+                        const int col = n0 + wpos[tn] + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                        if (col < g.N) orow[col] = acc[tm][tn][r];
+                    }
             }
         }
-        return;
     } else {
         constexpr int SC = (EPI == EPI_SWIGLU_FWD) ? 96 : (EPI == EPI_SWIGLU_BWD ? 128 : 64);
         constexpr int SROW = SC * 2 + 16;              // staging row stride in bytes
         constexpr int CPRS = SC / 8;                   // 16-byte chunks per staging row
         char* stg = smem + wave * (32 * SROW);
 #pragma unroll
-        for (int tm = 0; tm < TM; tm++) {
-            if (tm >= mtv) break;
+        for (int tm = 0; tm < MTV; tm++) {
             const int r_in = tm * 32 + lrow;
             // -- registers -> staging rows
             if constexpr (EPI == EPI_STORE) {
@@ -442,6 +454,40 @@ __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
                 }
             }
         }
+    }
+}
+
+template <int BM, int BN, int BK, int NS, bool WK, int EPI>
+__global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
+    static_assert(BM == 256 && BN == 256, "4 wavefronts x 64 columns, 8 strips of 32 rows");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    // ---- which tile ------------------------------------------------------------------------
+    const int n_mt = g.tile_meta[0];
+    const int G = g.group_m;
+    const int total = ((n_mt + G - 1) / G) * G * g.n_tiles_n;
+    const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
+    const int slot = blockIdx.x / kNumXcd;
+    if (slot >= per_xcd) return;
+    const int lt = (blockIdx.x % kNumXcd) * per_xcd + slot;
+    if (lt >= total) return;
+    const int grp = lt / (G * g.n_tiles_n);
+    const int rem = lt % (G * g.n_tiles_n);
+    const int nt = rem / G;
+    const int mt = grp * G + rem % G;
+    if (mt >= n_mt) return;
+    const int expert = g.tile_meta[4 + 4 * mt];
+    const int row0 = g.tile_meta[4 + 4 * mt + 1];
+    const int rows = g.tile_meta[4 + 4 * mt + 2];
+    switch ((rows + 31) >> 5) {       // 32-row strips that hold rows
+        case 1: xw_tile<BM, BN, BK, NS, WK, EPI, 1>(g, smem, expert, row0, rows, nt); break;
+        case 2: xw_tile<BM, BN, BK, NS, WK, EPI, 2>(g, smem, expert, row0, rows, nt); break;
+        case 3: xw_tile<BM, BN, BK, NS, WK, EPI, 3>(g, smem, expert, row0, rows, nt); break;
+        case 4: xw_tile<BM, BN, BK, NS, WK, EPI, 4>(g, smem, expert, row0, rows, nt); break;
+        case 5: xw_tile<BM, BN, BK, NS, WK, EPI, 5>(g, smem, expert, row0, rows, nt); break;
+        case 6: xw_tile<BM, BN, BK, NS, WK, EPI, 6>(g, smem, expert, row0, rows, nt); break;
+        case 7: xw_tile<BM, BN, BK, NS, WK, EPI, 7>(g, smem, expert, row0, rows, nt); break;
+        default: xw_tile<BM, BN, BK, NS, WK, EPI, 8>(g, smem, expert, row0, rows, nt); break;
     }
 }
 
@@ -552,33 +598,52 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
 
+    // software pipeline as in gemm_xw: fragments double buffered in registers
+    static_assert(KS % 2 == 0 && NS == 4, "fragment buffer parity and wait counts assume this");
+    bf16x8 pfr[2][4], qfr[2][4];
+    auto load_frags = [&](int stage, int ks, int buf) {
+        const char* pb = smem + stage * STAGE;
+        const char* qb = pb + PBYTES;
+#pragma unroll
+        for (int t = 0; t < 4; t++) {
+            pfr[buf][t] = PT::frag(pb, ks, wm * 128 + t * 32, lane);
+            qfr[buf][t] = PT::frag(qb, ks, wn * 128 + t * 32, lane);
+        }
+    };
+    auto mfmas = [&](int buf) {
+#pragma unroll
+        for (int a = 0; a < 4; a++)
+#pragma unroll
+            for (int b = 0; b < 4; b++)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pfr[buf][a], qfr[buf][b], acc[a][b], 0, 0, 0);
+    };
 #pragma unroll
     for (int s = 0; s < NS - 1; s++)
         if (s < nb) issue(s);
-
-    for (int kb = 0; kb < nb; kb++) {
-        const int younger = min(NS - 2, nb - 1 - kb);
-        if (younger >= NS - 2) wait_vmcnt<(NS - 2) * LPS>();
-        else if (younger == 1) wait_vmcnt<1 * LPS>();
+    {
+        const int y0 = min(NS - 2, nb - 1);
+        if (y0 >= 2) wait_vmcnt<2 * LPS>();
+        else if (y0 == 1) wait_vmcnt<1 * LPS>();
         else wait_vmcnt<0>();
-        __syncthreads();
-        if (kb + NS - 1 < nb) issue((kb + NS - 1) % NS);
-
-        const char* pb = smem + (kb % NS) * STAGE;
-        const char* qb = pb + PBYTES;
+    }
+    __syncthreads();
+    load_frags(0, 0, 0);
+    for (int kb = 0; kb < nb; kb++) {
+        const int stage = kb % NS;
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
-            bf16x8 pf[4], qf[4];
-#pragma unroll
-            for (int t = 0; t < 4; t++) {
-                pf[t] = PT::frag(pb, ks, wm * 128 + t * 32, lane);
-                qf[t] = PT::frag(qb, ks, wn * 128 + t * 32, lane);
+            if (ks + 1 < KS) {
+                load_frags(stage, ks + 1, (ks + 1) & 1);
+            } else {
+                if (nb - 1 - kb >= 2) wait_vmcnt<(NS - 3) * LPS>();
+                else wait_vmcnt<0>();
+                __syncthreads();
+                if (kb + NS - 1 < nb) issue((kb + NS - 1) % NS);
+                load_frags((kb + 1) % NS, 0, 0);
             }
-#pragma unroll
-            for (int a = 0; a < 4; a++)
-#pragma unroll
-                for (int b = 0; b < 4; b++)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[a], qf[b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(ks & 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
