@@ -33,7 +33,8 @@ ENTRY_POINTS = ("unipool_workspace_bytes", "unipool_last_error", "unipool_versio
 
 
 def lib_path() -> str:
-    return os.path.join(_PKG, "libunipool.so")
+    """Path of the shared library; UNIPOOL_LIB overrides the in-tree build."""
+    return os.environ.get("UNIPOOL_LIB") or os.path.join(_PKG, "libunipool.so")
 
 
 def load_library():

@@ -55,6 +55,7 @@ struct GemmArgs {
     const bf16* aux_b;
     int up_rows;          // EPI_SWIGLU_FWD: row offset of the up projection inside W_e (= d_ff)
     int group_m;          // row tiles walked together
+    const void* zeros;    // >= 16 readable zero bytes (reduction tail of KTAIL kernels)
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
 // 32-row strip, so a tile with few rows skips whole strips in all of them alike.  MTV = number
 // of strips that hold rows; the body is instantiated per MTV so that the K loop is straight-line
 // code and the accumulators of absent strips do not exist.
-template <int BM, int BN, int BK, int NS, bool WK, int EPI, int MTV>
+template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL, int MTV>
 __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int expert, int row0, int rows,
                                         int nt) {
     constexpr int TN = 2;
@@ -177,7 +178,8 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     constexpr int WI = BN * BK / 8 / 256;
     constexpr int LPS = XI + WI;            // loads per stage per wavefront
     constexpr int KS = BK / 16;
-    static_assert(KS % 2 == 0 && NS == 4, "fragment buffer parity and wait counts assume this");
+    static_assert(KS % 2 == 0, "fragment buffers alternate per slice and restart at 0 per stage");
+    static_assert(NS >= 2 && (NS - 1) * LPS < 64, "outstanding loads must fit the wait counter");
     using XT = KTile<BK>;
     using WTK = KTile<BK>;
     using WTN = NTile<BN>;
@@ -238,16 +240,6 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
         wstep = (size_t)BK * g.ldw * 2;
     }
 
-    auto issue = [&](int kt, int stage) {
-        const unsigned sb = lds0 + stage * STAGE;
-#pragma unroll
-        for (int i = 0; i < XI; i++)
-            glds16(xsrc[i] + (size_t)kt * BK * 2, sb + ((i * 4 + wave) * 64) * 16);
-#pragma unroll
-        for (int i = 0; i < WI; i++)
-            glds16(wsrc[i] + (size_t)kt * wstep, sb + XBYTES + ((i * 4 + wave) * 64) * 16);
-    };
-
     f32x16 acc[MTV][TN];
 #pragma unroll
     for (int tm = 0; tm < MTV; tm++)
@@ -266,67 +258,112 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
         wpos[1] = wave * 64 + 32;
     }
 
-    const int nk = g.K / BK;
+    const int nk = KTAIL ? (g.K + BK - 1) / BK : g.K / BK;
     // ---- software pipeline ----------------------------------------------------------------------
-    // Stages kt+1 .. kt+NS-2 are in flight while stage kt is multiplied.  Fragments are double
-    // buffered in registers: while the MFMAs of one 16-wide K slice run, the fragments of the next
-    // slice (or of the first slice of the next stage) are fetched from LDS.
+    // LDS holds NS stages of BK reduction indices.  While stage kt is multiplied, stages kt+1 ..
+    // kt+NS-1 are landing.  A stage is KS slices of 16 indices; fragments are double buffered in
+    // registers, and the LDS reads of the next slice are interleaved one by one with the MFMAs of
+    // the current slice (issue is in order: a burst of LDS reads would hold back the MFMAs behind
+    // it).  In the last slice of a stage the wavefronts meet once: stage kt+1 has landed, nobody
+    // reads stage kt any more, so its buffer takes the load of stage kt+NS, whose instructions
+    // are again spread between the MFMAs.
     bf16x8 wfr[2][TN], xfr[2][MTV];
-    auto load_frags = [&](int stage, int ks, int buf) {
+    constexpr int NM = MTV * TN;            // MFMAs per slice
+    constexpr int NL = MTV + TN;            // fragments per slice
+    auto frag_load = [&](int stage, int ks, int buf, int j) {
         const char* xb = smem + stage * STAGE;
         const char* wb = xb + XBYTES;
-#pragma unroll
-        for (int tn = 0; tn < TN; tn++) {
+        if (j < TN) {
             if constexpr (WK)
-                wfr[buf][tn] = lds_read16(wb + WTK::off(wpos[tn] + (lane & 31), ks * 2 + (lane >> 5)));
+                wfr[buf][j] = lds_read16(wb + WTK::off(wpos[j] + (lane & 31), ks * 2 + (lane >> 5)));
             else
-                wfr[buf][tn] = WTN::frag(wb, ks, wpos[tn], lane);
+                wfr[buf][j] = WTN::frag(wb, ks, wpos[j], lane);
+        } else {
+            xfr[buf][j - TN] = lds_read16(xb + XT::off((j - TN) * 32 + (lane & 31), ks * 2 + (lane >> 5)));
+        }
+    };
+    auto mfma_one = [&](int buf, int i) {
+        const int tm = i / TN, tn = i % TN;
+        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[buf][tn], xfr[buf][tm], acc[tm][tn], 0, 0, 0);
+    };
+    // KTAIL: K is not a multiple of BK; chunks past K come from a page of zeros in both operands
+    static_assert(!KTAIL || !WK, "the reduction tail is implemented for N-contiguous W only");
+    int xk[KTAIL ? XI : 1], wk[KTAIL ? WI : 1];   // first reduction index of the lane's chunk / row
+    if constexpr (KTAIL) {
+#pragma unroll
+        for (int i = 0; i < XI; i++) {
+            const int q = (i * 4 + wave) * 64 + lane;
+            xk[i] = ((q % XT::CPR) ^ XT::swz(q / XT::CPR)) * 8;
         }
 #pragma unroll
-        for (int tm = 0; tm < MTV; tm++)
-            xfr[buf][tm] = lds_read16(xb + XT::off(tm * 32 + (lane & 31), ks * 2 + (lane >> 5)));
-    };
-    auto mfmas = [&](int buf) {
-#pragma unroll
-        for (int tm = 0; tm < MTV; tm++)
-#pragma unroll
-            for (int tn = 0; tn < TN; tn++)
-                acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[buf][tn], xfr[buf][tm],
-                                                                      acc[tm][tn], 0, 0, 0);
-    };
-#pragma unroll
-    for (int s = 0; s < NS - 1; s++)
-        if (s < nk) issue(s, s);
-    {
-        const int y0 = min(NS - 2, nk - 1);
-        if (y0 >= 2) wait_vmcnt<2 * LPS>();
-        else if (y0 == 1) wait_vmcnt<1 * LPS>();
-        else wait_vmcnt<0>();
+        for (int i = 0; i < WI; i++) wk[i] = ((i * 4 + wave) * 64 + lane) / WTN::CPR;
     }
-    __syncthreads();
-    load_frags(0, 0, 0);
-    // One loop, one copy of the MFMA code (a second copy for the tail makes the register allocator
-    // move the accumulators between register files).  The sched_barriers keep the LDS reads of
-    // the next slice ahead of this slice's MFMAs: the scheduler would otherwise sink them next to
-    // their consumers and expose the LDS latency.
-    for (int kt = 0; kt < nk; kt++) {
+    auto issue_one = [&](int kt, int stage, int i) {
+        const unsigned sb = lds0 + stage * STAGE;
+        if (i < XI) {
+            const char* src = xsrc[i] + (size_t)kt * BK * 2;
+            if constexpr (KTAIL)
+                if (kt * BK + xk[i] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
+            glds16(src, sb + ((i * 4 + wave) * 64) * 16);
+        } else {
+            const char* src = wsrc[i - XI] + (size_t)kt * wstep;
+            if constexpr (KTAIL)
+                if (kt * BK + wk[i - XI] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
+            glds16(src, sb + XBYTES + (((i - XI) * 4 + wave) * 64) * 16);
+        }
+    };
+    // one stage; ISSUE: the load of stage kt+NS goes out
+    auto stage_body = [&](auto issue_c, int kt) {
+        constexpr bool ISSUE = decltype(issue_c)::value;
         const int stage = kt % NS;
 #pragma unroll
-        for (int ks = 0; ks < KS; ks++) {
-            if (ks + 1 < KS) {
-                load_frags(stage, ks + 1, (ks + 1) & 1);
-            } else {
-                // stage kt+1 must have landed; at most stage kt+2 may still be in flight
-                if (nk - 1 - kt >= 2) wait_vmcnt<(NS - 3) * LPS>();
-                else wait_vmcnt<0>();
-                __syncthreads();      // stage kt+1 is visible; every wavefront has left stage kt-1
-                if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt + NS - 1) % NS);
-                load_frags((kt + 1) % NS, 0, 0);      // after the last stage: unused, in bounds
+        for (int ks = 0; ks < KS - 1; ks++) {
+#pragma unroll
+            for (int i = 0; i < (NM > NL ? NM : NL); i++) {
+                if (i < NM) mfma_one(ks & 1, i);
+                if (i < NL) frag_load(stage, ks + 1, (ks + 1) & 1, i);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            mfmas(ks & 1);
+        }
+        // last slice: a quarter of its MFMAs covers the meeting of the wavefronts
+        constexpr int buf = (KS - 1) & 1;
+        constexpr int Q = NM / 4;
+#pragma unroll
+        for (int i = 0; i < Q; i++) mfma_one(buf, i);
+        __builtin_amdgcn_sched_barrier(0);
+        // stage kt+1 must have landed: the younger stages kt+2 .. kt+NS-1 may still be in flight
+        if constexpr (NS == 2) {
+            wait_vmcnt<0>();
+        } else {
+            if (nk - 2 - kt >= NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+            else wait_vmcnt<0>();
+        }
+        __syncthreads();
+        constexpr int REST = NM - Q;
+        constexpr int STEPS = REST > LPS ? (REST > NL ? REST : NL) : (LPS > NL ? LPS : NL);
+#pragma unroll
+        for (int i = 0; i < STEPS; i++) {
+            if (i < REST) mfma_one(buf, Q + i);
+            if (ISSUE && i < LPS) issue_one(kt + NS, stage, i);
+            if (i < NL) frag_load((kt + 1) % NS, 0, 0, i);     // after the last stage: unused, in bounds
             __builtin_amdgcn_sched_barrier(0);
         }
+    };
+#pragma unroll
+    for (int s = 0; s < NS; s++)
+        if (s < nk) {
+#pragma unroll
+            for (int i = 0; i < LPS; i++) issue_one(s, s, i);
+        }
+    if (nk > NS - 1) wait_vmcnt<(NS - 1) * LPS>();     // stage 0 has landed
+    else wait_vmcnt<0>();
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NL; j++) frag_load(0, 0, 0, j);
+    {
+        int kt = 0;
+        for (; kt + NS < nk; kt++) stage_body(std::integral_constant<bool, true>{}, kt);
+        for (; kt < nk; kt++) stage_body(std::integral_constant<bool, false>{}, kt);
     }
     __syncthreads();   // every wavefront is done with the operand tiles: LDS becomes staging space
 
@@ -457,7 +494,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     }
 }
 
-template <int BM, int BN, int BK, int NS, bool WK, int EPI>
+template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL>
 __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
     static_assert(BM == 256 && BN == 256, "4 wavefronts x 64 columns, 8 strips of 32 rows");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -480,14 +517,14 @@ __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
     const int row0 = g.tile_meta[4 + 4 * mt + 1];
     const int rows = g.tile_meta[4 + 4 * mt + 2];
     switch ((rows + 31) >> 5) {       // 32-row strips that hold rows
-        case 1: xw_tile<BM, BN, BK, NS, WK, EPI, 1>(g, smem, expert, row0, rows, nt); break;
-        case 2: xw_tile<BM, BN, BK, NS, WK, EPI, 2>(g, smem, expert, row0, rows, nt); break;
-        case 3: xw_tile<BM, BN, BK, NS, WK, EPI, 3>(g, smem, expert, row0, rows, nt); break;
-        case 4: xw_tile<BM, BN, BK, NS, WK, EPI, 4>(g, smem, expert, row0, rows, nt); break;
-        case 5: xw_tile<BM, BN, BK, NS, WK, EPI, 5>(g, smem, expert, row0, rows, nt); break;
-        case 6: xw_tile<BM, BN, BK, NS, WK, EPI, 6>(g, smem, expert, row0, rows, nt); break;
-        case 7: xw_tile<BM, BN, BK, NS, WK, EPI, 7>(g, smem, expert, row0, rows, nt); break;
-        default: xw_tile<BM, BN, BK, NS, WK, EPI, 8>(g, smem, expert, row0, rows, nt); break;
+        case 1: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 1>(g, smem, expert, row0, rows, nt); break;
+        case 2: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 2>(g, smem, expert, row0, rows, nt); break;
+        case 3: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 3>(g, smem, expert, row0, rows, nt); break;
+        case 4: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4>(g, smem, expert, row0, rows, nt); break;
+        case 5: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 5>(g, smem, expert, row0, rows, nt); break;
+        case 6: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 6>(g, smem, expert, row0, rows, nt); break;
+        case 7: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 7>(g, smem, expert, row0, rows, nt); break;
+        default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 8>(g, smem, expert, row0, rows, nt); break;
     }
 }
 
@@ -684,12 +721,14 @@ __global__ void reduce_partials_kernel(const float* __restrict__ part, int npart
 // ---------------------------------------------------------------------------------------------
 // launch helpers
 // ---------------------------------------------------------------------------------------------
-constexpr int kBM = 256, kBN = 256, kBK = 32, kNS = 4;
+constexpr int kBM = 256, kBN = 256, kBK = 64, kNS = 2;   // gemm_xw: 128-byte row segments per load
+constexpr int kPtqBK = 32, kPtqNS = 4;                      // gemm_ptq
 constexpr int kGemmLds = kNS * (kBM * kBK * 2 + kBN * kBK * 2);   // 128 KiB
+constexpr int kPtqLds = kPtqNS * 2 * kPtqBK * 256 * 2;            // 128 KiB
 
-template <bool WK, int EPI>
+template <bool WK, int EPI, bool KTAIL = false>
 hipError_t run_xw(GemmArgs a, int max_row_tiles, hipStream_t st) {
-    auto kern = gemm_xw_kernel<kBM, kBN, kBK, kNS, WK, EPI>;
+    auto kern = gemm_xw_kernel<kBM, kBN, kBK, kNS, WK, EPI, KTAIL>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -706,17 +745,17 @@ hipError_t run_xw(GemmArgs a, int max_row_tiles, hipStream_t st) {
 }
 
 hipError_t run_ptq(const PtqArgs& a, hipStream_t st) {
-    auto kern = gemm_ptq_kernel<kBK, kNS>;
+    auto kern = gemm_ptq_kernel<kPtqBK, kPtqNS>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kPtqLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int total = a.E * a.m_tiles * a.n_tiles;
     const int grid = cdiv(total, kNumXcd) * kNumXcd;
-    kern<<<grid, 256, kGemmLds, st>>>(a);
+    kern<<<grid, 256, kPtqLds, st>>>(a);
     return hipGetLastError();
 }
 
@@ -732,7 +771,7 @@ bool mfma_ffn_supported(const unipool_shape& s) {
 }
 
 bool mfma_router_supported(const unipool_shape& s) {
-    return s.dtype == UNIPOOL_BF16 && s.d_model % 64 == 0 && s.E % 32 == 0;
+    return s.dtype == UNIPOOL_BF16 && s.d_model % 64 == 0 && s.E % 8 == 0;
 }
 
 hipError_t mfma_logits(const unipool_shape& s, const void* x, const void* w, float* z,
@@ -845,7 +884,8 @@ hipError_t mfma_route_bwd_mm(const unipool_shape& s, const void* x, const void* 
     b.X = (const bf16*)dz; b.ldx = E;
     b.W = (const bf16*)w; b.w_stride = 0; b.ldw = d;
     b.K = E; b.N = d; b.n_tiles_n = cdiv(d, kBN);
-    b.tile_meta = meta2; b.out0 = dx; b.ldo = d; b.add = dx_accumulate;
+    b.tile_meta = meta2; b.out0 = dx; b.ldo = d; b.add = dx_accumulate; b.zeros = zeros;
+    if (E % kBK != 0) return run_xw<false, EPI_STORE, true>(b, cdiv(T, kBM), st);
     return run_xw<false, EPI_STORE>(b, cdiv(T, kBM), st);
 }
 
