@@ -164,7 +164,7 @@ int unipool_expert_ffn_bwd(const unipool_shape* shape, const void* dy_perm, cons
  * shared, the rows an expert received in different layers extend one reduction:
  *   d_w_gate_up[e] (+)= sum_l [dA|dB]^(l)_e^T X^(l)_e;   d_w_down[e] (+)= sum_l dY^(l)_e^T H^(l)_e.
  * The result equals n_layers calls of unipool_expert_ffn_bwd's accumulation.
- * in : device arrays of n_layers device pointers each: x_perm_l, d_act_l, act_h_l,
+ * in : n_layers in [1, 256]; device arrays of n_layers device pointers each: x_perm_l, d_act_l, act_h_l,
  *      dy_perm_l (tensors as in unipool_expert_ffn_bwd) and expert_offsets_l ([E+1] each).
  * out: d_w_gate_up, d_w_down float; accumulate != 0 adds to them, 0 overwrites them
  *      (experts with no rows in any layer are then set to zero).

@@ -278,7 +278,8 @@ int unipool_expert_wgrad(const unipool_shape* shape, int n_layers, const void* c
                          float* d_w_gate_up, float* d_w_down, int accumulate, void* ws,
                          size_t ws_bytes, void* stream) {
     PROLOGUE();
-    if (n_layers < 1) return set_error(UNIPOOL_EINVAL, "%s: n_layers=%d must be positive", __func__, n_layers);
+    if (n_layers < 1 || n_layers > 256)
+        return set_error(UNIPOOL_EINVAL, "%s: n_layers=%d outside [1, 256]", __func__, n_layers);
     REQUIRE_PTR(x_perm_l); REQUIRE_PTR(d_act_l); REQUIRE_PTR(act_h_l); REQUIRE_PTR(dy_perm_l);
     REQUIRE_PTR(expert_offsets_l); REQUIRE_PTR(d_w_gate_up); REQUIRE_PTR(d_w_down);
     NEED_WS();

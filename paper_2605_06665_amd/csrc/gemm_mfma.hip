@@ -36,6 +36,7 @@ constexpr int EPI_SWIGLU_BWD = 2;  // acc = dH; reads A, B; writes dA | dB
 constexpr int EPI_F32 = 3;         // float store
 
 constexpr int kNumXcd = 8;
+constexpr int kMaxPtqLayers = 256;   // layers chained in one weight-gradient reduction
 
 struct GemmArgs {
     const bf16* X;
@@ -571,12 +572,22 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
     const int wm = wave >> 1, wn = wave & 1;
     const unsigned lds0 = lds_addr_of(smem);
 
-    // number of K blocks over all layers
-    int nb = 0;
-    for (int l = 0; l < g.n_layers; l++) {
-        const int r = g.off[l][e + 1] - g.off[l][e];
-        nb += (r + BK - 1) / BK;
+    // Per-layer row range and operand pointers of expert e, fetched once into LDS: the K loop then
+    // advances from layer to layer without global loads of its own (whose wait counts would also
+    // wait for the operand loads in flight) and with wave-uniform control flow.
+    __shared__ int lds_r0[kMaxPtqLayers], lds_r1[kMaxPtqLayers];
+    __shared__ const bf16* lds_p[kMaxPtqLayers];
+    __shared__ const bf16* lds_q[kMaxPtqLayers];
+    for (int l = threadIdx.x; l < g.n_layers; l += 256) {
+        lds_r0[l] = g.off[l][e];
+        lds_r1[l] = g.off[l][e + 1];
+        lds_p[l] = reinterpret_cast<const bf16*>(g.P[l]);
+        lds_q[l] = reinterpret_cast<const bf16*>(g.Q[l]);
     }
+    __syncthreads();
+    int nb = 0;     // number of K blocks over all layers
+    for (int l = 0; l < g.n_layers; l++)
+        nb += (__builtin_amdgcn_readfirstlane(lds_r1[l] - lds_r0[l]) + BK - 1) / BK;
     float* otile = g.out + (long long)e * g.out_stride;
     if (nb == 0) {
         if (!g.accumulate) {
@@ -588,43 +599,42 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
         return;
     }
 
-    // lane geometry of the direct-to-LDS loads: slot q -> (k row, chunk)
-    int ld_krow[PI], ld_pcol[PI], ld_qcol[PI];
-#pragma unroll
-    for (int i = 0; i < PI; i++) {
-        const int q = (i * 4 + wave) * 64 + lane;
-        ld_krow[i] = q / PT::CPR;
-        const int cc = (q % PT::CPR) ^ PT::swz(ld_krow[i]);
-        ld_pcol[i] = min(m0 + cc * 8, g.mdim - 8);
-        ld_qcol[i] = min(n0 + cc * 8, g.ndim - 8);
-    }
+    // lane geometry of the direct-to-LDS loads: load i of a wavefront fills LDS slots
+    // (i*4 + wave)*64 + lane, i.e. K row 8*i + 2*wave + lane/32, chunk position lane%32.  The
+    // swizzle depends on (K row & 3) only, which is the same for all i.
+    const int krow0 = 2 * wave + (lane >> 5);
+    const int cc = (lane & 31) ^ PT::swz(krow0);
+    const int pcol = min(m0 + cc * 8, g.mdim - 8);
+    const int qcol = min(n0 + cc * 8, g.ndim - 8);
 
-    // load cursor
+    // load cursor over the rows of expert e, layer after layer
     int ld_layer = -1, ld_r = 0, ld_end = 0;
     const bf16* ld_p = nullptr;
     const bf16* ld_q = nullptr;
+    auto uniform_ptr = [](const bf16* p) {
+        const unsigned long long v = (unsigned long long)p;
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+        return reinterpret_cast<const bf16*>(((unsigned long long)hi << 32) | lo);
+    };
     auto next_block = [&]() {     // advance to the next non-empty K block
         while (ld_r >= ld_end) {
             ld_layer++;
-            ld_r = g.off[ld_layer][e];
-            ld_end = g.off[ld_layer][e + 1];
-            ld_p = reinterpret_cast<const bf16*>(g.P[ld_layer]);
-            ld_q = reinterpret_cast<const bf16*>(g.Q[ld_layer]);
+            ld_r = __builtin_amdgcn_readfirstlane(lds_r0[ld_layer]);
+            ld_end = __builtin_amdgcn_readfirstlane(lds_r1[ld_layer]);
+            ld_p = uniform_ptr(lds_p[ld_layer]) + pcol;
+            ld_q = uniform_ptr(lds_q[ld_layer]) + qcol;
         }
     };
-    auto issue = [&](int stage) {
-        next_block();
+    // load i (0..LPS-1) of the current K block: P rows for i < PI, Q rows after
+    auto issue_one = [&](int stage, int i) {
         const unsigned sb = lds0 + stage * STAGE;
-#pragma unroll
-        for (int i = 0; i < PI; i++) {
-            const int r = ld_r + ld_krow[i];
-            const bool ok = r < ld_end;
-            const void* ps = ok ? (const void*)(ld_p + (size_t)r * g.mdim + ld_pcol[i]) : g.zeros;
-            const void* qs = ok ? (const void*)(ld_q + (size_t)r * g.ndim + ld_qcol[i]) : g.zeros;
-            glds16(ps, sb + ((i * 4 + wave) * 64) * 16);
-            glds16(qs, sb + PBYTES + ((i * 4 + wave) * 64) * 16);
-        }
-        ld_r += BK;
+        const int ii = i < PI ? i : i - PI;
+        const int r = ld_r + krow0 + 8 * ii;
+        const void* src = g.zeros;
+        if (r < ld_end)
+            src = i < PI ? (const void*)(ld_p + (size_t)r * g.mdim) : (const void*)(ld_q + (size_t)r * g.ndim);
+        glds16(src, sb + (i < PI ? 0 : PBYTES) + ((ii * 4 + wave) * 64) * 16);
     };
 
     f32x16 acc[4][4];
@@ -635,73 +645,96 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
 
-    // software pipeline as in gemm_xw: fragments double buffered in registers
-    static_assert(KS % 2 == 0 && NS == 4, "fragment buffer parity and wait counts assume this");
+    // software pipeline as in gemm_xw
+    static_assert(KS % 2 == 0, "fragment buffers alternate per slice and restart at 0 per stage");
+    static_assert(NS >= 2 && (NS - 1) * LPS < 64, "outstanding loads must fit the wait counter");
     bf16x8 pfr[2][4], qfr[2][4];
-    auto load_frags = [&](int stage, int ks, int buf) {
+    auto frag_load = [&](int stage, int ks, int buf, int j) {
         const char* pb = smem + stage * STAGE;
-        const char* qb = pb + PBYTES;
-#pragma unroll
-        for (int t = 0; t < 4; t++) {
-            pfr[buf][t] = PT::frag(pb, ks, wm * 128 + t * 32, lane);
-            qfr[buf][t] = PT::frag(qb, ks, wn * 128 + t * 32, lane);
-        }
+        if (j < 4) pfr[buf][j] = PT::frag(pb, ks, wm * 128 + j * 32, lane);
+        else qfr[buf][j - 4] = PT::frag(pb + PBYTES, ks, wn * 128 + (j - 4) * 32, lane);
     };
-    auto mfmas = [&](int buf) {
-#pragma unroll
-        for (int a = 0; a < 4; a++)
-#pragma unroll
-            for (int b = 0; b < 4; b++)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pfr[buf][a], qfr[buf][b], acc[a][b], 0, 0, 0);
+    auto mfma_one = [&](int buf, int i) {
+        const int a = i >> 2, b = i & 3;
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pfr[buf][a], qfr[buf][b], acc[a][b], 0, 0, 0);
     };
-#pragma unroll
-    for (int s = 0; s < NS - 1; s++)
-        if (s < nb) issue(s);
-    {
-        const int y0 = min(NS - 2, nb - 1);
-        if (y0 >= 2) wait_vmcnt<2 * LPS>();
-        else if (y0 == 1) wait_vmcnt<1 * LPS>();
-        else wait_vmcnt<0>();
-    }
-    __syncthreads();
-    load_frags(0, 0, 0);
-    for (int kb = 0; kb < nb; kb++) {
+    auto stage_body = [&](auto issue_c, int kb) {
+        constexpr bool ISSUE = decltype(issue_c)::value;
         const int stage = kb % NS;
 #pragma unroll
-        for (int ks = 0; ks < KS; ks++) {
-            if (ks + 1 < KS) {
-                load_frags(stage, ks + 1, (ks + 1) & 1);
-            } else {
-                if (nb - 1 - kb >= 2) wait_vmcnt<(NS - 3) * LPS>();
-                else wait_vmcnt<0>();
-                __syncthreads();
-                if (kb + NS - 1 < nb) issue((kb + NS - 1) % NS);
-                load_frags((kb + 1) % NS, 0, 0);
+        for (int ks = 0; ks < KS - 1; ks++) {
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                mfma_one(ks & 1, i);
+                if (i < 8) frag_load(stage, ks + 1, (ks + 1) & 1, i);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            mfmas(ks & 1);
+        }
+        constexpr int buf = (KS - 1) & 1;
+#pragma unroll
+        for (int i = 0; i < 4; i++) mfma_one(buf, i);
+        __builtin_amdgcn_sched_barrier(0);
+        if (nb - 2 - kb >= NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+        else wait_vmcnt<0>();
+        __syncthreads();
+        if constexpr (ISSUE) next_block();
+#pragma unroll
+        for (int i = 0; i < 12; i++) {
+            mfma_one(buf, 4 + i);
+            if (ISSUE && i < LPS) issue_one(stage, i);
+            if (i < 8) frag_load((kb + 1) % NS, 0, 0, i);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (ISSUE) ld_r += BK;
+    };
+    static_assert(LPS <= 12, "load issue is spread over the last 12 MFMAs of a stage");
+#pragma unroll
+    for (int s = 0; s < NS; s++)
+        if (s < nb) {
+            next_block();
+#pragma unroll
+            for (int i = 0; i < LPS; i++) issue_one(s, i);
+            ld_r += BK;
+        }
+    if (nb > NS - 1) wait_vmcnt<(NS - 1) * LPS>();
+    else wait_vmcnt<0>();
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 8; j++) frag_load(0, 0, 0, j);
+    {
+        int kb = 0;
+        for (; kb + NS < nb; kb++) stage_body(std::integral_constant<bool, true>{}, kb);
+        for (; kb < nb; kb++) stage_body(std::integral_constant<bool, false>{}, kb);
     }
 
     // acc[a][b][r] = out[i = m0 + wm*128 + a*32 + 8*(r/4) + 4*(lane/32) + r%4][j = n0 + wn*128 + b*32 + lane%32]
+    // A wavefront store covers two rows of 32 consecutive floats.  When accumulating, the 16 old
+    // values of a 32x32 block are fetched together before any of them is added and written back.
 #pragma unroll
-    for (int a = 0; a < 4; a++)
+    for (int a = 0; a < 4; a++) {
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int i = m0 + wm * 128 + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (i < g.mdim) {
-                float* orow = otile + (size_t)i * g.ndim;
+        for (int b = 0; b < 4; b++) {
+            const int j = n0 + wn * 128 + b * 32 + (lane & 31);
+            const int i0 = m0 + wm * 128 + a * 32 + 4 * (lane >> 5);
+            float* base = otile + (size_t)i0 * g.ndim + j;
+            float old[16];
+            if (g.accumulate) {
 #pragma unroll
-                for (int b = 0; b < 4; b++) {
-                    const int j = n0 + wn * 128 + b * 32 + (lane & 31);
-                    if (j < g.ndim) {
-                        if (g.accumulate) orow[j] += acc[a][b][r];
-                        else orow[j] = acc[a][b][r];
-                    }
+                for (int r = 0; r < 16; r++) {
+                    const int di = 8 * (r >> 2) + (r & 3);
+                    old[r] = (j < g.ndim && i0 + di < g.mdim) ? base[(size_t)di * g.ndim] : 0.f;
                 }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; r++) old[r] = 0.f;
+            }
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const int di = 8 * (r >> 2) + (r & 3);
+                if (j < g.ndim && i0 + di < g.mdim) base[(size_t)di * g.ndim] = old[r] + acc[a][b][r];
             }
         }
+    }
 }
 
 __global__ void chunk_offsets_kernel(int T, int chunk_rows, int nchunks, int32_t* __restrict__ off) {
