@@ -36,6 +36,7 @@ constexpr int EPI_SWIGLU_BWD = 2;  // acc = dH; reads A, B; writes dA | dB
 constexpr int EPI_F32 = 3;         // float store
 
 constexpr int kNumXcd = 8;
+
 constexpr int kMaxPtqLayers = 256;   // layers chained in one weight-gradient reduction
 
 struct GemmArgs {
@@ -46,7 +47,8 @@ struct GemmArgs {
     int ldw;
     int K, N;             // reduction length; number of output columns (per half for SWIGLU_FWD)
     int n_tiles_n;
-    const int32_t* tile_meta;
+    int32_t* tile_meta;
+    int launch_slot;      // which of the table's tile counters this launch uses (0..3)
     void* out0;
     void* out1;
     void* out2;
@@ -131,8 +133,12 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// tile table: [0] = number of row tiles; entry i at 4+4i: expert, first row, rows in tile
+// tile table: [0] = number of row tiles; [16 .. 48) = tile counters of up to four launches (one per
+// XCD each), zeroed here; entry i at kTileBase + 4i: expert, first row, rows in tile
 // ---------------------------------------------------------------------------------------------
+constexpr int kTileBase = 64;
+constexpr int kSchedBase = 16;
+
 __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restrict__ offsets, int E,
                                                           int total_rows, int BM,
                                                           int32_t* __restrict__ meta) {
@@ -147,13 +153,14 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
         first[E] = run;
         meta[0] = run;
     }
+    if (threadIdx.x >= kSchedBase && threadIdx.x < kSchedBase + 4 * kNumXcd) meta[threadIdx.x] = 0;
     __syncthreads();
     for (int e = 0; e < E; e++) {
         const int r0 = offsets ? offsets[e] : 0;
         const int r1 = offsets ? offsets[e + 1] : total_rows;
         const int nt = first[e + 1] - first[e];
         for (int i = threadIdx.x; i < nt; i += 512) {
-            int32_t* m = meta + 4 + 4 * (first[e] + i);
+            int32_t* m = meta + kTileBase + 4 * (first[e] + i);
             m[0] = e;
             m[1] = r0 + i * BM;
             m[2] = min(BM, r1 - (r0 + i * BM));
@@ -174,13 +181,10 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     constexpr int TN = 2;
     constexpr int XBYTES = BM * BK * 2;
     constexpr int WBYTES = BN * BK * 2;
-    constexpr int STAGE = XBYTES + WBYTES;
     constexpr int XI = BM * BK / 8 / 256;   // direct-to-LDS loads per wavefront, X tile
     constexpr int WI = BN * BK / 8 / 256;
-    constexpr int LPS = XI + WI;            // loads per stage per wavefront
     constexpr int KS = BK / 16;
     static_assert(KS % 2 == 0, "fragment buffers alternate per slice and restart at 0 per stage");
-    static_assert(NS >= 2 && (NS - 1) * LPS < 64, "outstanding loads must fit the wait counter");
     using XT = KTile<BK>;
     using WTK = KTile<BK>;
     using WTN = NTile<BN>;
@@ -192,6 +196,10 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     // direct-to-LDS pipeline.  Making the inputs opaque here keeps every body self-contained.
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
+    expert = __builtin_amdgcn_readfirstlane(expert);
+    row0 = __builtin_amdgcn_readfirstlane(row0);
+    rows = __builtin_amdgcn_readfirstlane(rows);
+    nt = __builtin_amdgcn_readfirstlane(nt);
     asm volatile("" : "+s"(expert), "+s"(row0), "+s"(rows), "+s"(nt));
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -261,25 +269,30 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
 
     const int nk = KTAIL ? (g.K + BK - 1) / BK : g.K / BK;
     // ---- software pipeline ----------------------------------------------------------------------
-    // LDS holds NS stages of BK reduction indices.  While stage kt is multiplied, stages kt+1 ..
-    // kt+NS-1 are landing.  A stage is KS slices of 16 indices; fragments are double buffered in
-    // registers, and the LDS reads of the next slice are interleaved one by one with the MFMAs of
-    // the current slice (issue is in order: a burst of LDS reads would hold back the MFMAs behind
-    // it).  In the last slice of a stage the wavefronts meet once: stage kt+1 has landed, nobody
-    // reads stage kt any more, so its buffer takes the load of stage kt+NS, whose instructions
-    // are again spread between the MFMAs.
+    // LDS holds NSX stages of the X tile and NSW stages of the W tile (BK reduction indices each).
+    // X rows are shared by all column tiles of an expert and come from L2; W tiles are used by the
+    // one or two row tiles of an expert only and mostly come from HBM, so W is fetched one stage
+    // further ahead than X.  While stage kt is multiplied, X(kt+1) and W(kt+1), W(kt+2) are landing.
+    // A stage is KS slices of 16 indices; fragments are double buffered in registers, and the LDS
+    // reads of the next slice are interleaved one by one with the MFMAs of the current slice
+    // (issue is in order: a burst of LDS reads would hold back the MFMAs behind it).  In the last
+    // slice of a stage the wavefronts meet once: stage kt+1 has landed, nobody reads stage kt any
+    // more, so its buffers take the loads of X(kt+NSX) and W(kt+NSW), whose instructions are again
+    // spread between the MFMAs.
+    constexpr int NSX = NS, NSW = NS + 1;
+    constexpr int WBASE = NSX * XBYTES;
     bf16x8 wfr[2][TN], xfr[2][MTV];
     constexpr int NM = MTV * TN;            // MFMAs per slice
     constexpr int NL = MTV + TN;            // fragments per slice
-    auto frag_load = [&](int stage, int ks, int buf, int j) {
-        const char* xb = smem + stage * STAGE;
-        const char* wb = xb + XBYTES;
+    auto frag_load = [&](int kt, int ks, int buf, int j) {
         if (j < TN) {
+            const char* wb = smem + WBASE + (kt % NSW) * WBYTES;
             if constexpr (WK)
                 wfr[buf][j] = lds_read16(wb + WTK::off(wpos[j] + (lane & 31), ks * 2 + (lane >> 5)));
             else
                 wfr[buf][j] = WTN::frag(wb, ks, wpos[j], lane);
         } else {
+            const char* xb = smem + (kt % NSX) * XBYTES;
             xfr[buf][j - TN] = lds_read16(xb + XT::off((j - TN) * 32 + (lane & 31), ks * 2 + (lane >> 5)));
         }
     };
@@ -299,30 +312,28 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
 #pragma unroll
         for (int i = 0; i < WI; i++) wk[i] = ((i * 4 + wave) * 64 + lane) / WTN::CPR;
     }
-    auto issue_one = [&](int kt, int stage, int i) {
-        const unsigned sb = lds0 + stage * STAGE;
-        if (i < XI) {
-            const char* src = xsrc[i] + (size_t)kt * BK * 2;
-            if constexpr (KTAIL)
-                if (kt * BK + xk[i] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
-            glds16(src, sb + ((i * 4 + wave) * 64) * 16);
-        } else {
-            const char* src = wsrc[i - XI] + (size_t)kt * wstep;
-            if constexpr (KTAIL)
-                if (kt * BK + wk[i - XI] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
-            glds16(src, sb + XBYTES + (((i - XI) * 4 + wave) * 64) * 16);
-        }
+    auto issue_x = [&](int kt, int i) {
+        const char* src = xsrc[i] + (size_t)kt * BK * 2;
+        if constexpr (KTAIL)
+            if (kt * BK + xk[i] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
+        glds16(src, lds0 + (kt % NSX) * XBYTES + ((i * 4 + wave) * 64) * 16);
     };
-    // one stage; ISSUE: the load of stage kt+NS goes out
-    auto stage_body = [&](auto issue_c, int kt) {
-        constexpr bool ISSUE = decltype(issue_c)::value;
-        const int stage = kt % NS;
+    auto issue_w = [&](int kt, int i) {
+        const char* src = wsrc[i] + (size_t)kt * wstep;
+        if constexpr (KTAIL)
+            if (kt * BK + wk[i] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
+        glds16(src, lds0 + WBASE + (kt % NSW) * WBYTES + ((i * 4 + wave) * 64) * 16);
+    };
+    // one stage; IX / IW: the loads of X(kt+NSX) / W(kt+NSW) go out
+    auto stage_body = [&](auto ix_c, auto iw_c, int kt) {
+        constexpr bool IX = decltype(ix_c)::value;
+        constexpr bool IW = decltype(iw_c)::value;
 #pragma unroll
         for (int ks = 0; ks < KS - 1; ks++) {
 #pragma unroll
             for (int i = 0; i < (NM > NL ? NM : NL); i++) {
                 if (i < NM) mfma_one(ks & 1, i);
-                if (i < NL) frag_load(stage, ks + 1, (ks + 1) & 1, i);
+                if (i < NL) frag_load(kt, ks + 1, (ks + 1) & 1, i);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -332,39 +343,62 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
 #pragma unroll
         for (int i = 0; i < Q; i++) mfma_one(buf, i);
         __builtin_amdgcn_sched_barrier(0);
-        // stage kt+1 must have landed: the younger stages kt+2 .. kt+NS-1 may still be in flight
-        if constexpr (NS == 2) {
-            wait_vmcnt<0>();
-        } else {
-            if (nk - 2 - kt >= NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+        // X(kt+1) and W(kt+1) must have landed.  Loads complete in issue order and every batch is
+        // issued X first, so only the W(kt+2) .. W(kt+NSW-1) loads of later batches and the
+        // X(kt+2) .. loads may remain: with NSX = NSW-1 that is the last (NSW-2) W batches plus
+        // (NSX-2) X batches.
+        {
+            const int later = nk - 2 - kt;          // stages after kt+1
+            constexpr int FULL = (NSW - 2) * WI + (NSX - 2) * XI;
+            static_assert(FULL < 64, "outstanding loads must fit the wait counter");
+            if (later >= NSW - 2) wait_vmcnt<FULL>();
             else wait_vmcnt<0>();
         }
         __syncthreads();
         constexpr int REST = NM - Q;
-        constexpr int STEPS = REST > LPS ? (REST > NL ? REST : NL) : (LPS > NL ? LPS : NL);
+        constexpr int NI = (IX ? XI : 0) + (IW ? WI : 0);
+        constexpr int STEPS = REST > NI ? (REST > NL ? REST : NL) : (NI > NL ? NI : NL);
 #pragma unroll
         for (int i = 0; i < STEPS; i++) {
             if (i < REST) mfma_one(buf, Q + i);
-            if (ISSUE && i < LPS) issue_one(kt + NS, stage, i);
-            if (i < NL) frag_load((kt + 1) % NS, 0, 0, i);     // after the last stage: unused, in bounds
+            if constexpr (IX) {
+                if (i < XI) issue_x(kt + NSX, i);
+                else if (IW && i < XI + WI) issue_w(kt + NSW, i - XI);
+            } else if constexpr (IW) {
+                if (i < WI) issue_w(kt + NSW, i);
+            }
+            if (i < NL) frag_load(kt + 1, 0, 0, i);     // after the last stage: unused, in bounds
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    // prologue: X(0) W(0) X(1) W(1) ... X(NSX-1) W(NSX-1) W(NSW-1)
 #pragma unroll
-    for (int s = 0; s < NS; s++)
+    for (int s = 0; s < NSW; s++) {
+        if (s < NSX && s < nk) {
+#pragma unroll
+            for (int i = 0; i < XI; i++) issue_x(s, i);
+        }
         if (s < nk) {
 #pragma unroll
-            for (int i = 0; i < LPS; i++) issue_one(s, s, i);
+            for (int i = 0; i < WI; i++) issue_w(s, i);
         }
-    if (nk > NS - 1) wait_vmcnt<(NS - 1) * LPS>();     // stage 0 has landed
-    else wait_vmcnt<0>();
+    }
+    {
+        // stage 0 has landed when only the batches of stages 1 .. are outstanding
+        const int later = min(nk - 1, NSW - 1);
+        if (later >= NSW - 1) wait_vmcnt<(NSX - 1) * XI + (NSW - 1) * WI>();
+        else wait_vmcnt<0>();
+    }
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < NL; j++) frag_load(0, 0, 0, j);
     {
+        using T = std::integral_constant<bool, true>;
+        using F = std::integral_constant<bool, false>;
         int kt = 0;
-        for (; kt + NS < nk; kt++) stage_body(std::integral_constant<bool, true>{}, kt);
-        for (; kt < nk; kt++) stage_body(std::integral_constant<bool, false>{}, kt);
+        for (; kt + NSW < nk; kt++) stage_body(T{}, T{}, kt);
+        for (; kt + NSX < nk; kt++) stage_body(T{}, F{}, kt);
+        for (; kt < nk; kt++) stage_body(F{}, F{}, kt);
     }
     __syncthreads();   // every wavefront is done with the operand tiles: LDS becomes staging space
 
@@ -500,32 +534,44 @@ __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
     static_assert(BM == 256 && BN == 256, "4 wavefronts x 64 columns, 8 strips of 32 rows");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-    // ---- which tile ------------------------------------------------------------------------
+    // ---- persistent workgroups -----------------------------------------------------------------
+    // One workgroup per CU stays resident and takes tiles from a counter.  (With one 160 KB
+    // workgroup per CU and tiles of unequal length, the in-order hardware dispatch leaves CUs idle.)
+    // Each XCD has its own L2, so the tile list is cut into eight contiguous parts and a
+    // workgroup takes tiles of the part of the XCD it runs on: the row tiles of an expert, which
+    // share the expert's weights, and its column tiles, which share its rows, stay on one L2.
     const int n_mt = g.tile_meta[0];
     const int G = g.group_m;
     const int total = ((n_mt + G - 1) / G) * G * g.n_tiles_n;
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
-    const int slot = blockIdx.x / kNumXcd;
-    if (slot >= per_xcd) return;
-    const int lt = (blockIdx.x % kNumXcd) * per_xcd + slot;
-    if (lt >= total) return;
-    const int grp = lt / (G * g.n_tiles_n);
-    const int rem = lt % (G * g.n_tiles_n);
-    const int nt = rem / G;
-    const int mt = grp * G + rem % G;
-    if (mt >= n_mt) return;
-    const int expert = g.tile_meta[4 + 4 * mt];
-    const int row0 = g.tile_meta[4 + 4 * mt + 1];
-    const int rows = g.tile_meta[4 + 4 * mt + 2];
-    switch ((rows + 31) >> 5) {       // 32-row strips that hold rows
-        case 1: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 1>(g, smem, expert, row0, rows, nt); break;
-        case 2: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 2>(g, smem, expert, row0, rows, nt); break;
-        case 3: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 3>(g, smem, expert, row0, rows, nt); break;
-        case 4: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4>(g, smem, expert, row0, rows, nt); break;
-        case 5: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 5>(g, smem, expert, row0, rows, nt); break;
-        case 6: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 6>(g, smem, expert, row0, rows, nt); break;
-        case 7: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 7>(g, smem, expert, row0, rows, nt); break;
-        default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 8>(g, smem, expert, row0, rows, nt); break;
+    const int xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kNumXcd - 1);   // XCC_ID
+    const int lt_end = min(total, (xcd + 1) * per_xcd);
+    int32_t* counter = g.tile_meta + kSchedBase + g.launch_slot * kNumXcd + xcd;
+    for (;;) {
+        __syncthreads();              // the previous tile's staging space is free
+        if (threadIdx.x == 0) *reinterpret_cast<volatile int*>(smem) = atomicAdd(counter, 1);
+        __syncthreads();
+        const int lt = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(smem)) + xcd * per_xcd;
+        __syncthreads();
+        if (lt >= lt_end) break;
+        const int grp = lt / (G * g.n_tiles_n);
+        const int rem = lt % (G * g.n_tiles_n);
+        const int nt = rem / G;
+        const int mt = grp * G + rem % G;
+        if (mt >= n_mt) continue;
+        const int expert = g.tile_meta[kTileBase + 4 * mt];
+        const int row0 = g.tile_meta[kTileBase + 4 * mt + 1];
+        const int rows = g.tile_meta[kTileBase + 4 * mt + 2];
+        switch ((rows + 31) >> 5) {       // 32-row strips that hold rows
+            case 1: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 1>(g, smem, expert, row0, rows, nt); break;
+            case 2: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 2>(g, smem, expert, row0, rows, nt); break;
+            case 3: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 3>(g, smem, expert, row0, rows, nt); break;
+            case 4: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4>(g, smem, expert, row0, rows, nt); break;
+            case 5: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 5>(g, smem, expert, row0, rows, nt); break;
+            case 6: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 6>(g, smem, expert, row0, rows, nt); break;
+            case 7: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 7>(g, smem, expert, row0, rows, nt); break;
+            default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 8>(g, smem, expert, row0, rows, nt); break;
+        }
     }
 }
 
@@ -756,8 +802,20 @@ __global__ void reduce_partials_kernel(const float* __restrict__ part, int npart
 // ---------------------------------------------------------------------------------------------
 constexpr int kBM = 256, kBN = 256, kBK = 64, kNS = 2;   // gemm_xw: 128-byte row segments per load
 constexpr int kPtqBK = 32, kPtqNS = 4;                      // gemm_ptq
-constexpr int kGemmLds = kNS * (kBM * kBK * 2 + kBN * kBK * 2);   // 128 KiB
+constexpr int kGemmLds = kNS * kBM * kBK * 2 + (kNS + 1) * kBN * kBK * 2;   // 2 X stages + 3 W stages = 160 KiB
 constexpr int kPtqLds = kPtqNS * 2 * kPtqBK * 256 * 2;            // 128 KiB
+
+int num_cus() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t p;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess)
+            n = p.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
 
 template <bool WK, int EPI, bool KTAIL = false>
 hipError_t run_xw(GemmArgs a, int max_row_tiles, hipStream_t st) {
@@ -770,9 +828,8 @@ hipError_t run_xw(GemmArgs a, int max_row_tiles, hipStream_t st) {
         attr_set = true;
     }
     a.group_m = 2;
-    const int groups = cdiv(max_row_tiles, a.group_m);
-    const int total = groups * a.group_m * a.n_tiles_n;
-    const int grid = cdiv(total, kNumXcd) * kNumXcd;
+    (void)max_row_tiles;
+    const int grid = num_cus();
     kern<<<grid, 256, kGemmLds, st>>>(a);
     return hipGetLastError();
 }
@@ -798,6 +855,7 @@ hipError_t build_tiles(const int32_t* offsets, int E, int total_rows, int32_t* m
 }
 
 }  // namespace
+
 
 bool mfma_ffn_supported(const unipool_shape& s) {
     return s.dtype == UNIPOOL_BF16 && s.d_model % 64 == 0 && s.d_ff % 64 == 0;
@@ -838,7 +896,7 @@ hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_
     b.X = (const bf16*)h_out; b.ldx = f;
     b.W = (const bf16*)wd; b.w_stride = (long long)d * f; b.ldw = f;
     b.K = f; b.N = d; b.n_tiles_n = cdiv(d, kBN);
-    b.tile_meta = tile_meta; b.out0 = y; b.ldo = d;
+    b.tile_meta = tile_meta; b.launch_slot = 1; b.out0 = y; b.ldo = d;
     return run_xw<true, EPI_STORE>(b, max_tiles, st);
 }
 
@@ -861,7 +919,7 @@ hipError_t mfma_ffn_dgrad(const unipool_shape& s, const void* dy, const void* a_
     b.X = (const bf16*)d_act; b.ldx = 2 * f;
     b.W = (const bf16*)wgu; b.w_stride = 2LL * f * d; b.ldw = d;
     b.K = 2 * f; b.N = d; b.n_tiles_n = cdiv(d, kBN);
-    b.tile_meta = tile_meta; b.out0 = dx; b.ldo = d;
+    b.tile_meta = tile_meta; b.launch_slot = 1; b.out0 = dx; b.ldo = d;
     return run_xw<false, EPI_STORE>(b, max_tiles, st);
 }
 
