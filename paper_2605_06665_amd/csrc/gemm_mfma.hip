@@ -159,11 +159,15 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
         const int r0 = offsets ? offsets[e] : 0;
         const int r1 = offsets ? offsets[e + 1] : total_rows;
         const int nt = first[e + 1] - first[e];
+        // The rows of an expert are cut into equal tiles (multiples of 32 rows) rather than into
+        // full tiles plus a remainder: tiles that share an expert's weights then take equally long
+        // and stay in step, so the second reader of a weight tile still finds it in L2.
+        const int per = nt > 0 ? (((r1 - r0 + nt - 1) / nt + 31) / 32) * 32 : 0;
         for (int i = threadIdx.x; i < nt; i += 512) {
             int32_t* m = meta + kTileBase + 4 * (first[e] + i);
             m[0] = e;
-            m[1] = r0 + i * BM;
-            m[2] = min(BM, r1 - (r0 + i * BM));
+            m[1] = r0 + i * per;
+            m[2] = max(0, min(per, r1 - (r0 + i * per)));
         }
     }
 }
@@ -562,6 +566,7 @@ __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
         const int expert = g.tile_meta[kTileBase + 4 * mt];
         const int row0 = g.tile_meta[kTileBase + 4 * mt + 1];
         const int rows = g.tile_meta[kTileBase + 4 * mt + 2];
+        if (rows <= 0) continue;
         switch ((rows + 31) >> 5) {       // 32-row strips that hold rows
             case 1: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 1>(g, smem, expert, row0, rows, nt); break;
             case 2: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 2>(g, smem, expert, row0, rows, nt); break;
