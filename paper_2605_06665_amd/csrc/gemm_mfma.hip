@@ -142,33 +142,56 @@ constexpr int kSchedBase = 16;
 __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restrict__ offsets, int E,
                                                           int total_rows, int BM,
                                                           int32_t* __restrict__ meta) {
-    __shared__ int first[kMaxE + 1];
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int e = 0; e < E; e++) {
-            const int r = offsets ? offsets[e + 1] - offsets[e] : total_rows;
-            first[e] = run;
-            run += (r + BM - 1) / BM;
-        }
-        first[E] = run;
-        meta[0] = run;
+    __shared__ int first[kMaxE + 1];      // exclusive prefix sum of tiles per expert
+    __shared__ int scan[2][512];
+    const int t = threadIdx.x;
+    int r0 = 0, r1 = 0;
+    if (t < E) {
+        r0 = offsets ? offsets[t] : 0;
+        r1 = offsets ? offsets[t + 1] : total_rows;
     }
-    if (threadIdx.x >= kSchedBase && threadIdx.x < kSchedBase + 4 * kNumXcd) meta[threadIdx.x] = 0;
+    const int nt = (r1 - r0 + BM - 1) / BM;
+    // inclusive Hillis-Steele scan over 512 entries
+    scan[0][t] = nt;
     __syncthreads();
-    for (int e = 0; e < E; e++) {
-        const int r0 = offsets ? offsets[e] : 0;
-        const int r1 = offsets ? offsets[e + 1] : total_rows;
-        const int nt = first[e + 1] - first[e];
-        // The rows of an expert are cut into equal tiles (multiples of 32 rows) rather than into
-        // full tiles plus a remainder: tiles that share an expert's weights then take equally long
-        // and stay in step, so the second reader of a weight tile still finds it in L2.
+    int cur = 0;
+    for (int d = 1; d < 512; d <<= 1) {
+        scan[cur ^ 1][t] = scan[cur][t] + (t >= d ? scan[cur][t - d] : 0);
+        cur ^= 1;
+        __syncthreads();
+    }
+    const int my_first = scan[cur][t] - nt;
+    if (t < E) first[t] = my_first;
+    if (t == 0) {
+        first[E] = scan[cur][511];
+        meta[0] = scan[cur][511];
+    }
+    if (t >= kSchedBase && t < kSchedBase + 4 * kNumXcd) meta[t] = 0;
+    // The rows of an expert are cut into equal tiles (multiples of 32 rows) rather than into full
+    // tiles plus a remainder: tiles that share an expert's weights then take equally long and stay
+    // in step, so the second reader of a weight tile still finds it in L2.
+    if (t < E) {
         const int per = nt > 0 ? (((r1 - r0 + nt - 1) / nt + 31) / 32) * 32 : 0;
-        for (int i = threadIdx.x; i < nt; i += 512) {
-            int32_t* m = meta + kTileBase + 4 * (first[e] + i);
-            m[0] = e;
+        for (int i = 0; i < nt; i++) {
+            int32_t* m = meta + kTileBase + 4 * (my_first + i);
+            m[0] = t;
             m[1] = r0 + i * per;
             m[2] = max(0, min(per, r1 - (r0 + i * per)));
         }
+    }
+}
+
+// Row tiles of one ungrouped matrix (the router's GEMMs): tile i covers rows [i*BM, min(rows, (i+1)*BM)).
+__global__ void build_tiles_flat_kernel(int total_rows, int BM, int32_t* __restrict__ meta) {
+    const int n = (total_rows + BM - 1) / BM;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) meta[0] = n;
+    if (i >= kSchedBase && i < kSchedBase + 4 * kNumXcd) meta[i] = 0;
+    if (i < n) {
+        int32_t* m = meta + kTileBase + 4 * i;
+        m[0] = 0;
+        m[1] = i * BM;
+        m[2] = min(BM, total_rows - i * BM);
     }
 }
 
@@ -855,7 +878,12 @@ hipError_t run_ptq(const PtqArgs& a, hipStream_t st) {
 }
 
 hipError_t build_tiles(const int32_t* offsets, int E, int total_rows, int32_t* meta, hipStream_t st) {
-    build_tiles_kernel<<<1, 512, 0, st>>>(offsets, E, total_rows, kBM, meta);
+    if (offsets == nullptr) {
+        const int n = cdiv(total_rows, kBM);
+        build_tiles_flat_kernel<<<cdiv(max(n, 64), 256), 256, 0, st>>>(total_rows, kBM, meta);
+    } else {
+        build_tiles_kernel<<<1, 512, 0, st>>>(offsets, E, total_rows, kBM, meta);
+    }
     return hipGetLastError();
 }
 

@@ -4,8 +4,8 @@
 // without order-dependent atomics:
 //   1. hist    : one wavefront per chunk of 64 tokens builds, in LDS, a 64-bit token mask per
 //                expert (atomic OR, order-free) and writes the per-chunk histogram;
-//   2. scan    : exclusive scan of counts -> expert_offsets; per expert, running sum over the
-//                chunks turns the histograms into per-chunk base rows;
+//   2. scan    : exclusive scan of counts -> expert_offsets; per expert, an exclusive scan over
+//                the chunks turns the histograms into per-chunk base rows;
 //   3. scatter : every chunk rebuilds its masks; the rank of a token inside its chunk is the
 //                popcount of the lower lanes' bits; row = chunk base + rank;
 //   4. copy    : one wavefront per token reads the row once and writes its k copies with
@@ -48,31 +48,45 @@ __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __rest
     for (int e = lane; e < E; e += 64) chunk_hist[(size_t)chunk * E + e] = __popcll(mask[e]);
 }
 
-// One block.  Thread e: offsets by a serial scan done by thread 0 (E <= 512), then the
-// running sum over chunks for expert e.
-__global__ __launch_bounds__(512) void permute_scan_kernel(const int32_t* __restrict__ counts,
-                                                           int E, int nchunks,
-                                                           int32_t* __restrict__ expert_offsets,
-                                                           int32_t* __restrict__ chunk_hist) {
-    __shared__ int off[kMaxE + 1];
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int e = 0; e < E; e++) {
-            off[e] = run;
-            run += counts[e];
-        }
-        off[E] = run;
-    }
+// expert_offsets = exclusive prefix sum of counts (one block, parallel scan over <= 512 experts).
+__global__ __launch_bounds__(512) void permute_offsets_kernel(const int32_t* __restrict__ counts, int E,
+                                                              int32_t* __restrict__ expert_offsets) {
+    __shared__ int scan[2][512];
+    const int t = threadIdx.x;
+    const int c = t < E ? counts[t] : 0;
+    scan[0][t] = c;
     __syncthreads();
-    for (int e = threadIdx.x; e <= E; e += 512) expert_offsets[e] = off[e];
-    const int e = threadIdx.x;
-    if (e < E) {
-        int run = off[e];
-        for (int c = 0; c < nchunks; c++) {
-            const int h = chunk_hist[(size_t)c * E + e];
-            chunk_hist[(size_t)c * E + e] = run;
-            run += h;
+    int cur = 0;
+    for (int d = 1; d < 512; d <<= 1) {
+        scan[cur ^ 1][t] = scan[cur][t] + (t >= d ? scan[cur][t - d] : 0);
+        cur ^= 1;
+        __syncthreads();
+    }
+    if (t < E) expert_offsets[t] = scan[cur][t] - c;
+    if (t == 0) expert_offsets[E] = scan[cur][511];
+}
+
+// One block per expert: exclusive scan of its per-chunk histogram, started at the expert's offset.
+__global__ __launch_bounds__(256) void permute_scan_kernel(const int32_t* __restrict__ expert_offsets,
+                                                           int E, int nchunks,
+                                                           int32_t* __restrict__ chunk_hist) {
+    __shared__ int scan[2][256];
+    const int e = blockIdx.x, t = threadIdx.x;
+    int carry = expert_offsets[e];
+    for (int c0 = 0; c0 < nchunks; c0 += 256) {
+        const int c = c0 + t;
+        const int h = c < nchunks ? chunk_hist[(size_t)c * E + e] : 0;
+        scan[0][t] = h;
+        __syncthreads();
+        int cur = 0;
+        for (int d = 1; d < 256; d <<= 1) {
+            scan[cur ^ 1][t] = scan[cur][t] + (t >= d ? scan[cur][t - d] : 0);
+            cur ^= 1;
+            __syncthreads();
         }
+        if (c < nchunks) chunk_hist[(size_t)c * E + e] = carry + scan[cur][t] - h;
+        carry += scan[cur][255];
+        __syncthreads();
     }
 }
 
@@ -152,7 +166,8 @@ hipError_t launch_permute(const unipool_shape& s, const void* x, const int32_t* 
     const int nblocks = cdiv(nchunks, kChunkWaves);
     const size_t lds = (size_t)kChunkWaves * s.E * sizeof(unsigned long long);
     permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_idx, s.T, s.E, s.k, chunk_hist);
-    permute_scan_kernel<<<1, 512, 0, st>>>(counts, s.E, nchunks, expert_offsets, chunk_hist);
+    permute_offsets_kernel<<<1, 512, 0, st>>>(counts, s.E, expert_offsets);
+    permute_scan_kernel<<<s.E, 256, 0, st>>>(expert_offsets, s.E, nchunks, chunk_hist);
     permute_scatter_kernel<<<nblocks, 256, lds, st>>>(topk_idx, s.T, s.E, s.k, chunk_hist,
                                                       row_of_slot, slot_of_row);
     const size_t row_bytes = (size_t)s.d_model * (s.dtype == UNIPOOL_BF16 ? 2 : 4);

@@ -86,19 +86,33 @@ __global__ __launch_bounds__(256) void route_score_topk_kernel(
     }
 }
 
-__global__ __launch_bounds__(512) void route_finalize_kernel(
+// One block per expert: the block partials are summed by a fixed-shape tree (deterministic).
+__global__ __launch_bounds__(256) void route_finalize_kernel(
     const int32_t* __restrict__ cnt_part, const float* __restrict__ psum_part, int nblocks, int E,
     int32_t* __restrict__ counts, float* __restrict__ psum) {
-    const int e = threadIdx.x;
-    if (e >= E) return;
+    __shared__ int rc[256];
+    __shared__ float rp[256];
+    const int e = blockIdx.x, t = threadIdx.x;
     int c = 0;
     float p = 0.f;
-    for (int b = 0; b < nblocks; b++) {
+    for (int b = t; b < nblocks; b += 256) {
         c += cnt_part[(size_t)b * E + e];
         p += psum_part[(size_t)b * E + e];
     }
-    counts[e] = c;
-    psum[e] = p;
+    rc[t] = c;
+    rp[t] = p;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (t < s) {
+            rc[t] += rc[t + s];
+            rp[t] += rp[t + s];
+        }
+        __syncthreads();
+    }
+    if (t == 0) {
+        counts[e] = rc[0];
+        psum[e] = rp[0];
+    }
 }
 
 template <typename TA>
@@ -167,12 +181,19 @@ __global__ __launch_bounds__(256) void route_bwd_dz_kernel(
         dsigma_part[blockIdx.x] = ((lds_ds[0] + lds_ds[1]) + lds_ds[2]) + lds_ds[3];
 }
 
-__global__ void dsigma_finalize_kernel(const float* __restrict__ part, int n, float* __restrict__ out) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        float v = 0.f;
-        for (int i = 0; i < n; i++) v += part[i];
-        out[0] = v;
+__global__ __launch_bounds__(256) void dsigma_finalize_kernel(const float* __restrict__ part, int n,
+                                                              float* __restrict__ out) {
+    __shared__ float red[256];
+    const int t = threadIdx.x;
+    float v = 0.f;
+    for (int i = t; i < n; i += 256) v += part[i];
+    red[t] = v;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (t < s) red[t] += red[t + s];
+        __syncthreads();
     }
+    if (t == 0) out[0] = red[0];
 }
 
 }  // namespace
@@ -183,7 +204,7 @@ hipError_t launch_route_score_topk(const unipool_shape& s, const float* logits, 
     const int nblocks = cdiv(s.T, kRouterTokensPerBlock);
     route_score_topk_kernel<<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps,
                                                      topk_idx, topk_gate, cnt_part, psum_part);
-    route_finalize_kernel<<<1, 512, 0, st>>>(cnt_part, psum_part, nblocks, s.E, counts, psum);
+    route_finalize_kernel<<<s.E, 256, 0, st>>>(cnt_part, psum_part, nblocks, s.E, counts, psum);
     return hipGetLastError();
 }
 
@@ -199,7 +220,7 @@ hipError_t launch_route_bwd_dz(const unipool_shape& s, const float* logits, cons
         route_bwd_dz_kernel<float><<<nblocks, 256, 0, st>>>(logits, topk_idx, dgate, aux_coef, s.T,
                                                             s.E, s.k, s.sigma, s.c, s.eps,
                                                             (float*)dz, dsigma_part);
-    dsigma_finalize_kernel<<<1, 64, 0, st>>>(dsigma_part, nblocks, d_sigma);
+    dsigma_finalize_kernel<<<1, 256, 0, st>>>(dsigma_part, nblocks, d_sigma);
     return hipGetLastError();
 }
 
