@@ -21,6 +21,11 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# HBM bytes per gemm_xw launch from rocprofv3 counters (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
+# of the 1 GiB copy below), averaged over the four expert-FFN launches of a layer; see
+# profiles/gemm_counters_C5.txt.  Not measured for the other workloads.
+MEASURED_XW_TRAFFIC_BYTES = {"C5": 7.8e9}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -30,7 +35,7 @@ def parse():
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--wgrad", default="pool", choices=["pool", "layer"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--oracle-tokens", type=int, default=512)
+    ap.add_argument("--oracle-tokens", type=int, default=1024)
     return ap.parse_args()
 
 
@@ -81,6 +86,12 @@ def main():
     wgu = torch.cat([wg, wu], dim=1).contiguous()
     sigmas = [w.sigma] * w.L
     ps = PoolStep(w.T, w.d, w.f, w.E, w.k, w.L, dtype, w.c, w.eps, w.alpha, device=dev, wgrad=a.wgrad)
+    # one plain device-to-device copy of known size (1 GiB read + 1 GiB write): the reference
+    # against which the HBM byte counters of a profiler run are scaled
+    cal_src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    del cal_src, cal_dst
     torch.cuda.synchronize()
 
     for _ in range(a.warmup):
@@ -139,7 +150,9 @@ def main():
                    "tokens_per_layer": w.T, "skew": w.skew, "wgrad": a.wgrad,
                    "tokens_counted": "L*T token-layer evaluations per step"},
         "roofline": {"bound": "mfma", "achieved": xw_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": xw_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": xw_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_XW_TRAFFIC_BYTES.get(a.workload),
+                     "algorithmic_bytes_per_launch": (12.0 * w.E * w.d * w.f + 8.0 * S * w.d + 16.0 * S * w.f) / 4.0,
                      "kernel": "gemm_xw (grouped bf16 GEMM: gate-up, down, dH, dX)",
                      "avg_launch_ms": avg_xw_ms, "launches": n_xw,
                      "flops_per_launch": xw_flops_per_launch},
