@@ -152,7 +152,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": xw_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": xw_tflops / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_XW_TRAFFIC_BYTES.get(a.workload),
-                     "algorithmic_bytes_per_launch": (12.0 * w.E * w.d * w.f + 8.0 * S * w.d + 16.0 * S * w.f) / 4.0,
+                     "algorithmic_bytes_per_launch": (12.0 * w.E * w.d * w.f + 8.0 * S * w.d + 20.0 * S * w.f) / 4.0,
                      "kernel": "gemm_xw (grouped bf16 GEMM: gate-up, down, dH, dX)",
                      "avg_launch_ms": avg_xw_ms, "launches": n_xw,
                      "flops_per_launch": xw_flops_per_launch},
