@@ -1,0 +1,159 @@
+"""GPU parity at the benchmark's full shapes (C2 .. C5), in the launch configuration bench.py times
+(whole steps through the step driver, pooled weight gradient), with two layers sharing the pool.
+
+The integer results, the router and the pool loss are compared in full; expert-FFN results, their
+gradients and the weight gradients are compared on samples that the oracle computes one by one from
+the same inputs (for a stage deep in the chain, from the GPU's own upstream tensors, so that each
+kernel is judged on its own arithmetic).  Inputs are drawn on the device; the oracle gets host copies."""
+import numpy as np
+import pytest
+
+from oracle import unipool_oracle as O
+from synth import workloads as W
+from tests.gpu_util import TOL, host, near_tie_tokens, rel_err
+
+pytestmark = pytest.mark.gpu
+
+L_TEST = 2
+N_TOK = 24          # sampled tokens per layer for the expert path
+N_COL = 3           # sampled weight-gradient rows per sampled expert
+
+
+def f64(t):
+    return host(t).astype(np.float64)
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C4z", "C5"])
+def test_full_size_step(name):
+    import torch
+    import paper_2605_06665_amd as U
+    from paper_2605_06665_amd.pipeline import PoolStep
+
+    w = W.WORKLOADS[name].scaled(L=L_TEST)
+    dev = torch.device("cuda:0")
+    tol = TOL[w.dtype]
+    xs = [W.gen_x_torch(w, l, dev) for l in range(w.L)]
+    wrs = [W.gen_w_router_torch(w, l, dev) for l in range(w.L)]
+    gs = [W.gen_grad_out_torch(w, l, dev) for l in range(w.L)]
+    wg, wu, wd = W.gen_pool_weights_torch(w, dev)
+    wgu = torch.cat([wg, wu], dim=1).contiguous()
+    sig = [1.0 + 0.05 * l for l in range(w.L)]
+    ps = PoolStep(w.T, w.d, w.f, w.E, w.k, w.L, U.BF16, w.c, w.eps, w.alpha, device=dev, wgrad="pool")
+    ps.step(xs, wrs, sig, wgu, wd, gs)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(123)
+    T, k, E, d, f = w.T, w.k, w.E, w.d, w.f
+
+    counts_ref, psum_ref = [], []
+    for l in range(w.L):
+        st = ps.layers[l]
+        x, wr = f64(xs[l]), f64(wrs[l])
+        # ---- router: full comparison
+        r = O.route(x, wr, k, sig[l], w.c, w.eps)
+        gi = host(st.topk_idx)
+        tie = near_tie_tokens(r["z"], k)
+        assert tie.mean() < 1e-2
+        assert np.array_equal(gi[~tie], r["idx"][~tie]), "top-k indices differ outside near-ties"
+        assert all(len(set(row)) == k for row in gi[tie].tolist())
+        assert rel_err(host(st.logits), r["z"]) <= tol
+        assert rel_err(host(st.topk_gate)[~tie], r["gate"][~tie]) <= tol
+        gcounts = host(ps.counts[l])
+        assert np.array_equal(gcounts, np.bincount(gi.ravel(), minlength=E)) and int(gcounts.sum()) == T * k
+        assert rel_err(host(ps.psum[l]), r["psum"]) <= tol
+        counts_ref.append(gcounts)
+        psum_ref.append(host(ps.psum[l]))
+        # ---- permutation: full, bit exact, from the GPU's own selection
+        off, ros, sor = O.permutation(gi, E)
+        assert np.array_equal(host(st.offsets), off)
+        assert np.array_equal(host(st.row_of_slot), ros)
+        assert np.array_equal(host(st.slot_of_row), sor)
+        rows = rng.choice(w.S, size=256, replace=False)
+        xp = st.x_perm[torch.from_numpy(rows).to(dev)]
+        assert torch.equal(xp, xs[l][torch.from_numpy(sor[rows] // k).to(dev)])       # bitwise row copies
+        # ---- expert path on sampled tokens
+        toks = rng.choice(T, size=N_TOK, replace=False)
+        gate = host(st.topk_gate)
+        coef = f64(ps.aux_coef)
+        dgate_gpu = host(st.dgate)
+        dz_tok = O.route_bwd(x[toks], wr, r["z"][toks].astype(np.float32), gi[toks], dgate_gpu[toks], coef,
+                             sig[l], w.c, w.eps)
+        dx_router = dz_tok[0]
+        slot = l                                          # pooled mode keeps dy / d_act per layer
+        err = dict(a=0.0, b=0.0, h=0.0, y=0.0, out=0.0, dy=0.0, dgate=0.0, dact=0.0, dxp=0.0, dx=0.0)
+        if l == 0:
+            err["dxp_gpu"] = 0.0     # the driver's dx_perm buffer still holds layer 0 (processed last)
+        scale = dict.fromkeys(err, 1e-30)
+
+        def upd(key, got, ref):
+            err[key] = max(err[key], float(np.max(np.abs(got - ref))))
+            scale[key] = max(scale[key], float(np.max(np.abs(ref))))
+
+        for ti, t in enumerate(toks.tolist()):
+            out_ref = np.zeros(d)
+            dx_ref = dx_router[ti].copy()
+            for j in range(k):
+                e, row = int(gi[t, j]), int(ros[t, j])
+                wge, wue, wde = f64(wg[e]), f64(wu[e]), f64(wd[e])
+                a, b, h, y = O.expert_apply(x[t][None], wge, wue, wde)
+                upd("a", f64(st.act_a[row]), a[0]); upd("b", f64(st.act_b[row]), b[0])
+                upd("h", f64(st.act_h[row]), h[0]); upd("y", f64(st.y_perm[row]), y[0])
+                y_gpu = f64(st.y_perm[row])
+                out_ref += gate[t, j] * y_gpu             # combine judged on the GPU's y_perm
+                g_t = f64(gs[l][t])
+                upd("dy", f64(ps._dy[slot][row]), gate[t, j] * g_t)
+                upd("dgate", np.array([dgate_gpu[t, j]]), np.array([float(g_t @ y_gpu)]))
+                # dgrad from the GPU's saved activations and its dy row
+                dy_row, a_s, b_s = f64(ps._dy[slot][row]), f64(st.act_a[row]), f64(st.act_b[row])
+                dh = dy_row @ wde
+                da = dh * b_s * O.silu_grad(a_s)
+                db = dh * O.silu(a_s)
+                dact_gpu = f64(ps._dact[slot][row])
+                upd("dact", dact_gpu, np.concatenate([da, db]))
+                # dx_perm is overwritten per layer in the driver: recompute what combine must have seen
+                dxp = dact_gpu[:f] @ wge + dact_gpu[f:] @ wue
+                dx_ref += dxp
+                upd("dxp", dxp, da @ wge + db @ wue)
+                if l == 0:
+                    upd("dxp_gpu", f64(ps._dxp[row]), dxp)
+            upd("out", f64(st.out[t]), out_ref)
+            upd("dx", f64(st.dx[t]), dx_ref)
+        for key in err:
+            assert err[key] <= tol * scale[key], (name, l, key, err[key], scale[key])
+        # ---- router gradients: full
+        dxr, dwr, dsig, _ = O.route_bwd(x, wr, host(st.logits), gi, dgate_gpu, coef, sig[l], w.c, w.eps)
+        assert rel_err(host(st.d_w_router), dwr) <= tol
+        assert abs(float(host(st.d_sigma)[0]) - dsig) <= tol * max(abs(dsig), 1e-3)
+
+    # ---- pool loss: full, from the GPU's statistics
+    pc, fbar, loss, coef = O.pool_aux_loss(np.stack(counts_ref), np.stack(psum_ref), T, k, w.alpha)
+    assert np.array_equal(host(ps.pool_counts), pc) and int(pc.sum()) == w.L * T * k
+    assert rel_err(host(ps.fbar), fbar) <= 1e-6 and rel_err(host(ps.aux_coef), coef) <= 1e-6
+    assert abs(float(host(ps.loss)[0]) - loss) <= 1e-5 * abs(loss)
+
+    # ---- pooled weight gradient on sampled experts and rows, from the GPU's own operands
+    tot = np.stack(counts_ref).sum(axis=0)
+    order = np.argsort(tot)
+    nonempty = order[tot[order] > 0]
+    picks = {int(nonempty[-1]), int(nonempty[0]), int(rng.integers(0, E)), int(rng.integers(0, E))}
+    empty = order[tot[order] == 0]
+    if len(empty):
+        e0 = int(empty[0])
+        assert not ps.d_w_gate_up[e0].any() and not ps.d_w_down[e0].any()
+    for e in sorted(picks):
+        ns = rng.choice(2 * f, size=N_COL, replace=False)
+        cs = rng.choice(d, size=N_COL, replace=False)
+        ref_gu = np.zeros((N_COL, d))
+        ref_d = np.zeros((N_COL, f))
+        for l in range(w.L):
+            st = ps.layers[l]
+            r0, r1 = int(host(st.offsets)[e]), int(host(st.offsets)[e + 1])
+            if r1 == r0:
+                continue
+            xp, hh = f64(st.x_perm[r0:r1]), f64(st.act_h[r0:r1])
+            dact, dy = f64(ps._dact[l][r0:r1]), f64(ps._dy[l][r0:r1])
+            ref_gu += dact[:, ns].T @ xp
+            ref_d += dy[:, cs].T @ hh
+        got_gu = f64(ps.d_w_gate_up[e][torch.from_numpy(ns).to(dev)])
+        got_d = f64(ps.d_w_down[e][torch.from_numpy(cs).to(dev)])
+        assert rel_err(got_gu, ref_gu) <= tol, (name, e, "dw_gate_up")
+        assert rel_err(got_d, ref_d) <= tol, (name, e, "dw_down")
