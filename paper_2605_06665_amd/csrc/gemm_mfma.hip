@@ -198,27 +198,32 @@ __global__ void build_tiles_flat_kernel(int total_rows, int BM, int32_t* __restr
 // ---------------------------------------------------------------------------------------------
 // gemm_xw
 // ---------------------------------------------------------------------------------------------
-// One 256 x 256 output tile.  The four wavefronts split the columns (64 each) and all own every
-// 32-row strip, so a tile with few rows skips whole strips in all of them alike.  MTV = number
-// of strips that hold rows; the body is instantiated per MTV so that the K loop is straight-line
-// code and the accumulators of absent strips do not exist.
+// One 256 x 256 output tile, eight wavefronts (two per SIMD).  Wavefront (wm, wn) owns the 64
+// columns of group wn and every second 32-row strip starting at wm; both wavefronts of a column
+// group sit on the same SIMD, so a SIMD always carries the same share of the tile, however many
+// strips hold rows.  MTV = strips of THIS wavefront that hold rows (0..4); the body is instantiated
+// per MTV so that the K loop is straight-line code and absent strips have no accumulators.
+constexpr int kXwWaves = 8;
+constexpr int kXwThreads = kXwWaves * 64;
+
 template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL, int MTV>
 __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int expert, int row0, int rows,
                                         int nt) {
+    constexpr int NW = kXwWaves;
     constexpr int TN = 2;
     constexpr int XBYTES = BM * BK * 2;
     constexpr int WBYTES = BN * BK * 2;
-    constexpr int XI = BM * BK / 8 / 256;   // direct-to-LDS loads per wavefront, X tile
-    constexpr int WI = BN * BK / 8 / 256;
+    constexpr int XI = BM * BK / 8 / (NW * 64);   // direct-to-LDS loads per wavefront, X tile
+    constexpr int WI = BN * BK / 8 / (NW * 64);
     constexpr int KS = BK / 16;
     static_assert(KS % 2 == 0, "fragment buffers alternate per slice and restart at 0 per stage");
+    static_assert(BM == 256 && BN == 256 && NW == 8, "2 x 4 wavefronts, strips interleaved by 2");
     using XT = KTile<BK>;
     using WTK = KTile<BK>;
     using WTN = NTile<BN>;
-    using std::integral_constant;
 
     // The per-MTV bodies are alternatives of one switch.  Their set-up code is identical, and if
-    // the compiler merges it in front of the switch the merged values stay live across all eight
+    // the compiler merges it in front of the switch the merged values stay live across all the
     // bodies and spill; spill code is scratch traffic, whose wait counts would then serialise the
     // direct-to-LDS pipeline.  Making the inputs opaque here keeps every body self-contained.
     int tid = threadIdx.x;
@@ -229,29 +234,34 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     nt = __builtin_amdgcn_readfirstlane(nt);
     asm volatile("" : "+s"(expert), "+s"(row0), "+s"(rows), "+s"(nt));
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave & 3, wm = wave >> 2;
     const unsigned lds0 = lds_addr_of(smem);
     const bf16* We = g.W + (long long)expert * g.w_stride;
     const int n0 = nt * BN;                 // first column of the tile (plain epilogues)
     const int f0 = nt * (BN / 2);           // first column per half (SWIGLU_FWD)
+    const int strips = (rows + 31) >> 5;    // strips of the tile that hold rows
 
     // ---- per-lane source pointers of the direct-to-LDS loads ----------------------------------
-    // (rows of absent strips are loaded too, from the last valid row: they are never multiplied)
+    // Load i of a wavefront fills LDS chunks (i*NW + wave)*64 .. +63: 8 rows of 128 bytes.  Loads
+    // whose rows lie in strips without rows are left out (xload[i] false, wave-uniform).
     const char* xsrc[XI];
+    bool xload[XI];
 #pragma unroll
     for (int i = 0; i < XI; i++) {
-        const int q = (i * 4 + wave) * 64 + lane;
+        const int q = (i * NW + wave) * 64 + lane;
         const int row = q / XT::CPR;
         const int cc = (q % XT::CPR) ^ XT::swz(row);
         const int grow = row0 + min(row, rows - 1);
         xsrc[i] = reinterpret_cast<const char*>(g.X + (size_t)grow * g.ldx + cc * 8);
+        xload[i] = ((i * NW + wave) * 64 / XT::CPR) < strips * 32;
     }
     const char* wsrc[WI];
     size_t wstep;                           // bytes per K step
     if constexpr (WK) {
 #pragma unroll
         for (int i = 0; i < WI; i++) {
-            const int q = (i * 4 + wave) * 64 + lane;
+            const int q = (i * NW + wave) * 64 + lane;
             const int row = q / WTK::CPR;
             const int cc = (q % WTK::CPR) ^ WTK::swz(row);
             int wrow;
@@ -267,7 +277,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     } else {
 #pragma unroll
         for (int i = 0; i < WI; i++) {
-            const int q = (i * 4 + wave) * 64 + lane;
+            const int q = (i * NW + wave) * 64 + lane;
             const int krow = q / WTN::CPR;
             const int cc = (q % WTN::CPR) ^ WTN::swz(krow);
             const int col = min(n0 + cc * 8, g.N - 8);
@@ -276,7 +286,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
         wstep = (size_t)BK * g.ldw * 2;
     }
 
-    f32x16 acc[MTV][TN];
+    f32x16 acc[MTV > 0 ? MTV : 1][TN];
 #pragma unroll
     for (int tm = 0; tm < MTV; tm++)
 #pragma unroll
@@ -287,11 +297,11 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     // LDS rows (K-contiguous W) or columns (N-contiguous W) of this wavefront's two fragments
     int wpos[TN];
     if constexpr (EPI == EPI_SWIGLU_FWD) {
-        wpos[0] = wave * 32;
-        wpos[1] = BN / 2 + wave * 32;
+        wpos[0] = wn * 32;
+        wpos[1] = BN / 2 + wn * 32;
     } else {
-        wpos[0] = wave * 64;
-        wpos[1] = wave * 64 + 32;
+        wpos[0] = wn * 64;
+        wpos[1] = wn * 64 + 32;
     }
 
     const int nk = KTAIL ? (g.K + BK - 1) / BK : g.K / BK;
@@ -308,9 +318,9 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     // spread between the MFMAs.
     constexpr int NSX = NS, NSW = NS + 1;
     constexpr int WBASE = NSX * XBYTES;
-    bf16x8 wfr[2][TN], xfr[2][MTV];
-    constexpr int NM = MTV * TN;            // MFMAs per slice
-    constexpr int NL = MTV + TN;            // fragments per slice
+    bf16x8 wfr[2][TN], xfr[2][MTV > 0 ? MTV : 1];
+    constexpr int NM = MTV * TN;                    // MFMAs per slice
+    constexpr int NL = MTV > 0 ? MTV + TN : 0;      // fragments per slice
     auto frag_load = [&](int kt, int ks, int buf, int j) {
         if (j < TN) {
             const char* wb = smem + WBASE + (kt % NSW) * WBYTES;
@@ -320,7 +330,8 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
                 wfr[buf][j] = WTN::frag(wb, ks, wpos[j], lane);
         } else {
             const char* xb = smem + (kt % NSX) * XBYTES;
-            xfr[buf][j - TN] = lds_read16(xb + XT::off((j - TN) * 32 + (lane & 31), ks * 2 + (lane >> 5)));
+            const int strip = wm + 2 * (j - TN);
+            xfr[buf][j - TN] = lds_read16(xb + XT::off(strip * 32 + (lane & 31), ks * 2 + (lane >> 5)));
         }
     };
     auto mfma_one = [&](int buf, int i) {
@@ -333,23 +344,24 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     if constexpr (KTAIL) {
 #pragma unroll
         for (int i = 0; i < XI; i++) {
-            const int q = (i * 4 + wave) * 64 + lane;
+            const int q = (i * NW + wave) * 64 + lane;
             xk[i] = ((q % XT::CPR) ^ XT::swz(q / XT::CPR)) * 8;
         }
 #pragma unroll
-        for (int i = 0; i < WI; i++) wk[i] = ((i * 4 + wave) * 64 + lane) / WTN::CPR;
+        for (int i = 0; i < WI; i++) wk[i] = ((i * NW + wave) * 64 + lane) / WTN::CPR;
     }
     auto issue_x = [&](int kt, int i) {
+        if (!xload[i]) return;
         const char* src = xsrc[i] + (size_t)kt * BK * 2;
         if constexpr (KTAIL)
             if (kt * BK + xk[i] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
-        glds16(src, lds0 + (kt % NSX) * XBYTES + ((i * 4 + wave) * 64) * 16);
+        glds16(src, lds0 + (kt % NSX) * XBYTES + ((i * NW + wave) * 64) * 16);
     };
     auto issue_w = [&](int kt, int i) {
         const char* src = wsrc[i] + (size_t)kt * wstep;
         if constexpr (KTAIL)
             if (kt * BK + wk[i] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
-        glds16(src, lds0 + WBASE + (kt % NSW) * WBYTES + ((i * 4 + wave) * 64) * 16);
+        glds16(src, lds0 + WBASE + (kt % NSW) * WBYTES + ((i * NW + wave) * 64) * 16);
     };
     // one stage; IX / IW: the loads of X(kt+NSX) / W(kt+NSW) go out
     auto stage_body = [&](auto ix_c, auto iw_c, int kt) {
@@ -371,14 +383,11 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
         for (int i = 0; i < Q; i++) mfma_one(buf, i);
         __builtin_amdgcn_sched_barrier(0);
         // X(kt+1) and W(kt+1) must have landed.  Loads complete in issue order and every batch is
-        // issued X first, so only the W(kt+2) .. W(kt+NSW-1) loads of later batches and the
-        // X(kt+2) .. loads may remain: with NSX = NSW-1 that is the last (NSW-2) W batches plus
-        // (NSX-2) X batches.
+        // issued X first, so only the W loads of the batches after stage kt+1 may remain
+        // (NSX = 2: no younger X batch exists).
         {
-            const int later = nk - 2 - kt;          // stages after kt+1
-            constexpr int FULL = (NSW - 2) * WI + (NSX - 2) * XI;
-            static_assert(FULL < 64, "outstanding loads must fit the wait counter");
-            if (later >= NSW - 2) wait_vmcnt<FULL>();
+            static_assert(NSX == 2 && NSW == 3, "wait counts below");
+            if (nk - 2 - kt >= 1) wait_vmcnt<WI>();
             else wait_vmcnt<0>();
         }
         __syncthreads();
@@ -398,7 +407,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // prologue: X(0) W(0) X(1) W(1) ... X(NSX-1) W(NSX-1) W(NSW-1)
+    // prologue: X(0) W(0) X(1) W(1) W(2)
 #pragma unroll
     for (int s = 0; s < NSW; s++) {
         if (s < NSX && s < nk) {
@@ -410,12 +419,10 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
             for (int i = 0; i < WI; i++) issue_w(s, i);
         }
     }
-    {
-        // stage 0 has landed when only the batches of stages 1 .. are outstanding
-        const int later = min(nk - 1, NSW - 1);
-        if (later >= NSW - 1) wait_vmcnt<(NSX - 1) * XI + (NSW - 1) * WI>();
-        else wait_vmcnt<0>();
-    }
+    // stage 0 has landed when at most the two W batches of stages 1 and 2 are outstanding (the X
+    // batch of stage 1, which may be shorter than XI loads, then has landed too: stricter than needed)
+    if (nk >= NSW) wait_vmcnt<(NSW - 1) * WI>();
+    else wait_vmcnt<0>();
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < NL; j++) frag_load(0, 0, 0, j);
@@ -430,7 +437,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     __syncthreads();   // every wavefront is done with the operand tiles: LDS becomes staging space
 
     // ---- epilogue ---------------------------------------------------------------------------------
-    // acc[tm][tn][r] = C[row tm*32 + lane%32][col wpos-relative 8*(r/4) + 4*(lane/32) + r%4]
+    // acc[tm][tn][r] = C[row (wm + 2 tm)*32 + lane%32][col wpos-relative 8*(r/4) + 4*(lane/32) + r%4]
     const int lrow = lane & 31;
     const int lhalf = lane >> 5;
 
@@ -438,7 +445,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
         float* out = reinterpret_cast<float*>(g.out0);
 #pragma unroll
         for (int tm = 0; tm < MTV; tm++) {
-            const int r_in = tm * 32 + lrow;
+            const int r_in = (wm + 2 * tm) * 32 + lrow;
             if (r_in < rows) {
                 float* orow = out + (size_t)(row0 + r_in) * g.ldo;
 #pragma unroll
@@ -457,7 +464,8 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
         char* stg = smem + wave * (32 * SROW);
 #pragma unroll
         for (int tm = 0; tm < MTV; tm++) {
-            const int r_in = tm * 32 + lrow;
+            const int strip0 = (wm + 2 * tm) * 32;     // first row of the strip inside the tile
+            const int r_in = strip0 + lrow;
             // -- registers -> staging rows
             if constexpr (EPI == EPI_STORE) {
 #pragma unroll
@@ -492,7 +500,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
                         const int c = tn * 32 + 8 * q + 4 * lhalf;     // column inside the wave's 64
-                        const int col = n0 + wave * 64 + c;
+                        const int col = n0 + wn * 64 + c;
                         float da[4] = {0.f, 0.f, 0.f, 0.f}, db[4] = {0.f, 0.f, 0.f, 0.f};
                         if (rok && col < g.N) {
                             union { uint2 u; bf16 h[4]; } av, bv;
@@ -517,12 +525,12 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
                 const int id = it * 64 + lane;
                 const int srow = id / CPRS;
                 const int ch = id % CPRS;
-                const int rr = tm * 32 + srow;
+                const int rr = strip0 + srow;
                 if (rr >= rows) continue;
                 const uint4 v = *reinterpret_cast<const uint4*>(stg + srow * SROW + ch * 16);
                 const size_t grow = (size_t)(row0 + rr);
                 if constexpr (EPI == EPI_STORE) {
-                    const int col = n0 + wave * 64 + ch * 8;
+                    const int col = n0 + wn * 64 + ch * 8;
                     if (col < g.N) {
                         bf16* dst = reinterpret_cast<bf16*>(g.out0) + grow * g.ldo + col;
                         if (g.add) {
@@ -538,14 +546,14 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
                     }
                 } else if constexpr (EPI == EPI_SWIGLU_FWD) {
                     const int which = ch >> 2;
-                    const int col = f0 + wave * 32 + (ch & 3) * 8;
+                    const int col = f0 + wn * 32 + (ch & 3) * 8;
                     if (col < g.N) {
                         bf16* base = reinterpret_cast<bf16*>(which == 0 ? g.out0 : (which == 1 ? g.out1 : g.out2));
                         *reinterpret_cast<uint4*>(base + grow * g.ldo + col) = v;
                     }
                 } else {
                     const int which = ch >> 3;
-                    const int col = n0 + wave * 64 + (ch & 7) * 8;
+                    const int col = n0 + wn * 64 + (ch & 7) * 8;
                     if (col < g.N) {
                         bf16* dst = reinterpret_cast<bf16*>(g.out0) + grow * g.ldo + which * g.N + col;
                         *reinterpret_cast<uint4*>(dst) = v;
@@ -557,8 +565,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
 }
 
 template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL>
-__global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
-    static_assert(BM == 256 && BN == 256, "4 wavefronts x 64 columns, 8 strips of 32 rows");
+__global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     // ---- persistent workgroups -----------------------------------------------------------------
@@ -574,6 +581,7 @@ __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
     const int xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kNumXcd - 1);   // XCC_ID
     const int lt_end = min(total, (xcd + 1) * per_xcd);
     int32_t* counter = g.tile_meta + kSchedBase + g.launch_slot * kNumXcd + xcd;
+    const int wm = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8);        // wavefronts 4..7: odd strips
     for (;;) {
         __syncthreads();              // the previous tile's staging space is free
         if (threadIdx.x == 0) *reinterpret_cast<volatile int*>(smem) = atomicAdd(counter, 1);
@@ -590,15 +598,14 @@ __global__ __launch_bounds__(256) void gemm_xw_kernel(const GemmArgs g) {
         const int row0 = g.tile_meta[kTileBase + 4 * mt + 1];
         const int rows = g.tile_meta[kTileBase + 4 * mt + 2];
         if (rows <= 0) continue;
-        switch ((rows + 31) >> 5) {       // 32-row strips that hold rows
+        // strips wm, wm+2, ... of this wavefront that hold rows; every body runs the same barriers
+        const int strips = (rows + 31) >> 5;
+        switch (max(0, (strips - wm + 1) >> 1)) {
+            case 0: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 0>(g, smem, expert, row0, rows, nt); break;
             case 1: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 1>(g, smem, expert, row0, rows, nt); break;
             case 2: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 2>(g, smem, expert, row0, rows, nt); break;
             case 3: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 3>(g, smem, expert, row0, rows, nt); break;
-            case 4: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4>(g, smem, expert, row0, rows, nt); break;
-            case 5: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 5>(g, smem, expert, row0, rows, nt); break;
-            case 6: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 6>(g, smem, expert, row0, rows, nt); break;
-            case 7: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 7>(g, smem, expert, row0, rows, nt); break;
-            default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 8>(g, smem, expert, row0, rows, nt); break;
+            default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4>(g, smem, expert, row0, rows, nt); break;
         }
     }
 }
@@ -858,7 +865,7 @@ hipError_t run_xw(GemmArgs a, int max_row_tiles, hipStream_t st) {
     a.group_m = 2;
     (void)max_row_tiles;
     const int grid = num_cus();
-    kern<<<grid, 256, kGemmLds, st>>>(a);
+    kern<<<grid, kXwThreads, kGemmLds, st>>>(a);
     return hipGetLastError();
 }
 
