@@ -32,8 +32,9 @@ template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // RNE
 
-__device__ __forceinline__ float silu_f(float a) { return a / (1.0f + __expf(-a)); }
-__device__ __forceinline__ float logistic_f(float a) { return 1.0f / (1.0f + __expf(-a)); }
+// 1 / (1 + e^-a) with the hardware reciprocal (1 ulp) instead of an IEEE division
+__device__ __forceinline__ float logistic_f(float a) { return __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
+__device__ __forceinline__ float silu_f(float a) { return a * logistic_f(a); }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -39,6 +39,29 @@ constexpr int kNumXcd = 8;
 
 constexpr int kMaxPtqLayers = 256;   // layers chained in one weight-gradient reduction
 
+// Profiling builds (-DUNIPOOL_PHASE_TIMES) add up, per workgroup, the time the first wavefront
+// spends in the three phases of a gemm_xw tile (100 MHz ticks): pipeline fill, K loop, epilogue; one row per
+// workgroup and launch slot.
+#ifdef UNIPOOL_PHASE_TIMES
+__device__ unsigned long long g_phase_times[1024][8];
+#define PHASE_STAMP(var) const long long var = wall_clock64()
+#define PHASE_COMMIT(t0, t1, t2, t3)                                                         \
+    if (threadIdx.x == 0 && blockIdx.x < 256) {                                              \
+        unsigned long long* pt_ = g_phase_times[blockIdx.x + 256 * (g.launch_slot & 3)];     \
+        pt_[0] += (unsigned long long)((t1) - (t0));                                         \
+        pt_[1] += (unsigned long long)((t2) - (t1));                                         \
+        pt_[2] += (unsigned long long)((t3) - (t2));                                         \
+        pt_[3] += 1ull;                                                                      \
+        pt_[4] += (unsigned long long)acc_wait_;                                             \
+        pt_[5] += (unsigned long long)acc_bar_;                                              \
+        pt_[6] += (unsigned long long)acc_cyc_;                                              \
+    }
+#define PHASE_CLOCK(var) const long long var = clock64()
+#else
+#define PHASE_STAMP(var)
+#define PHASE_COMMIT(t0, t1, t2, t3)
+#endif
+
 struct GemmArgs {
     const bf16* X;
     int ldx;
@@ -233,6 +256,10 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     rows = __builtin_amdgcn_readfirstlane(rows);
     nt = __builtin_amdgcn_readfirstlane(nt);
     asm volatile("" : "+s"(expert), "+s"(row0), "+s"(rows), "+s"(nt));
+    PHASE_STAMP(t_begin);
+#ifdef UNIPOOL_PHASE_TIMES
+    long long acc_wait_ = 0, acc_bar_ = 0, acc_cyc_ = 0;
+#endif
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave & 3, wm = wave >> 2;
@@ -363,16 +390,44 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
             if (kt * BK + wk[i] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
         glds16(src, lds0 + WBASE + (kt % NSW) * WBYTES + ((i * NW + wave) * 64) * 16);
     };
-    // one stage; IX / IW: the loads of X(kt+NSX) / W(kt+NSW) go out
+    // One stage.  IX / IW: the loads of X(kt+1) / W(kt+2) go out during this stage, into the buffers
+    // that stage kt-1 has released.  They are spread over the slices before the meeting point, X in
+    // the first half (it has to land within this stage) and W in the second: a wavefront whose load
+    // finds the address unit's queue full stands still, MFMAs included, so a burst of loads from all
+    // wavefronts at once would cost the matrix cores the whole time the queue takes to drain.
     auto stage_body = [&](auto ix_c, auto iw_c, int kt) {
         constexpr bool IX = decltype(ix_c)::value;
         constexpr bool IW = decltype(iw_c)::value;
+        constexpr int SPS = NM > NL ? NM : NL;        // slots per slice
+        constexpr int SL = (KS - 1) * SPS;            // slots before the last slice
+        if constexpr (SL == 0) {
+            if constexpr (IX) {
+#pragma unroll
+                for (int u = 0; u < XI; u++) issue_x(kt + 1, u);
+            }
+            if constexpr (IW) {
+#pragma unroll
+                for (int u = 0; u < WI; u++) issue_w(kt + 2, u);
+            }
+        }
 #pragma unroll
         for (int ks = 0; ks < KS - 1; ks++) {
 #pragma unroll
-            for (int i = 0; i < (NM > NL ? NM : NL); i++) {
+            for (int i = 0; i < SPS; i++) {
                 if (i < NM) mfma_one(ks & 1, i);
                 if (i < NL) frag_load(kt, ks + 1, (ks + 1) & 1, i);
+                constexpr int H = SL / 2;
+                const int slot = ks * SPS + i;
+                if constexpr (IX) {
+#pragma unroll
+                    for (int u = 0; u < XI; u++)
+                        if (u * H / XI == slot) issue_x(kt + 1, u);
+                }
+                if constexpr (IW) {
+#pragma unroll
+                    for (int u = 0; u < WI; u++)
+                        if (H + u * (SL - H) / WI == slot) issue_w(kt + 2, u);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -382,27 +437,29 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
 #pragma unroll
         for (int i = 0; i < Q; i++) mfma_one(buf, i);
         __builtin_amdgcn_sched_barrier(0);
-        // X(kt+1) and W(kt+1) must have landed.  Loads complete in issue order and every batch is
-        // issued X first, so only the W loads of the batches after stage kt+1 may remain
-        // (NSX = 2: no younger X batch exists).
+        // X(kt+1) and W(kt+1) must have landed.  Loads complete in issue order and every stage
+        // issues X first, so only the W loads of stage kt+2 may remain (NSX = 2: no younger X batch).
+#ifdef UNIPOOL_PHASE_TIMES
+        PHASE_CLOCK(c0_);
+#endif
         {
             static_assert(NSX == 2 && NSW == 3, "wait counts below");
             if (nk - 2 - kt >= 1) wait_vmcnt<WI>();
             else wait_vmcnt<0>();
         }
+#ifdef UNIPOOL_PHASE_TIMES
+        PHASE_CLOCK(c1_);
+#endif
         __syncthreads();
+#ifdef UNIPOOL_PHASE_TIMES
+        PHASE_CLOCK(c2_);
+        acc_wait_ += c1_ - c0_;
+        acc_bar_ += c2_ - c1_;
+#endif
         constexpr int REST = NM - Q;
-        constexpr int NI = (IX ? XI : 0) + (IW ? WI : 0);
-        constexpr int STEPS = REST > NI ? (REST > NL ? REST : NL) : (NI > NL ? NI : NL);
 #pragma unroll
-        for (int i = 0; i < STEPS; i++) {
+        for (int i = 0; i < (REST > NL ? REST : NL); i++) {
             if (i < REST) mfma_one(buf, Q + i);
-            if constexpr (IX) {
-                if (i < XI) issue_x(kt + NSX, i);
-                else if (IW && i < XI + WI) issue_w(kt + NSW, i - XI);
-            } else if constexpr (IW) {
-                if (i < WI) issue_w(kt + NSW, i);
-            }
             if (i < NL) frag_load(kt + 1, 0, 0, i);     // after the last stage: unused, in bounds
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -424,17 +481,28 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     if (nk >= NSW) wait_vmcnt<(NSW - 1) * WI>();
     else wait_vmcnt<0>();
     __syncthreads();
+    PHASE_STAMP(t_filled);
+#ifdef UNIPOOL_PHASE_TIMES
+    PHASE_CLOCK(cl0_);
+#endif
 #pragma unroll
     for (int j = 0; j < NL; j++) frag_load(0, 0, 0, j);
     {
         using T = std::integral_constant<bool, true>;
         using F = std::integral_constant<bool, false>;
-        int kt = 0;
-        for (; kt + NSW < nk; kt++) stage_body(T{}, T{}, kt);
-        for (; kt + NSX < nk; kt++) stage_body(T{}, F{}, kt);
+        // stage 0: the prologue has issued X(1) and W(2) already
+        stage_body(F{}, F{}, 0);
+        int kt = 1;
+        for (; kt + 2 < nk; kt++) stage_body(T{}, T{}, kt);
+        for (; kt + 1 < nk; kt++) stage_body(T{}, F{}, kt);
         for (; kt < nk; kt++) stage_body(F{}, F{}, kt);
     }
     __syncthreads();   // every wavefront is done with the operand tiles: LDS becomes staging space
+    PHASE_STAMP(t_looped);
+#ifdef UNIPOOL_PHASE_TIMES
+    PHASE_CLOCK(cl1_);
+    acc_cyc_ = cl1_ - cl0_;
+#endif
 
     // ---- epilogue ---------------------------------------------------------------------------------
     // acc[tm][tn][r] = C[row (wm + 2 tm)*32 + lane%32][col wpos-relative 8*(r/4) + 4*(lane/32) + r%4]
@@ -461,11 +529,33 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
         constexpr int SC = (EPI == EPI_SWIGLU_FWD) ? 96 : (EPI == EPI_SWIGLU_BWD ? 128 : 64);
         constexpr int SROW = SC * 2 + 16;              // staging row stride in bytes
         constexpr int CPRS = SC / 8;                   // 16-byte chunks per staging row
-        char* stg = smem + wave * (32 * SROW);
+        // SWIGLU_BWD also stages the saved activations A and B of a strip: they are fetched as whole
+        // 128-byte row segments (one request per cache line instead of one per 16 bytes in the
+        // accumulator layout), a strip ahead, and picked up from LDS in the accumulator layout.
+        constexpr int AROW = 64 * 2 + 16;               // A / B staging row stride in bytes
+        constexpr int WSTG = 32 * SROW + (EPI == EPI_SWIGLU_BWD ? 2 * 32 * AROW : 0);
+        static_assert(kXwWaves * WSTG <= NSX * XBYTES + NSW * WBYTES, "staging fits the operand buffers");
+        char* stg = smem + wave * WSTG;
+        [[maybe_unused]] char* stga = stg + 32 * SROW;
+        [[maybe_unused]] char* stgb = stga + 32 * AROW;
+        [[maybe_unused]] uint4 av0, av1, av2, av3, bv0, bv1, bv2, bv3;
+        // the 64 columns of a wavefront are inside N or outside as a whole (N is a multiple of 64)
+        [[maybe_unused]] const bool cols_ok = n0 + wn * 64 < g.N;
+#define UNIPOOL_LOAD_AB1(TMX, IT)                                                                  \
+    {                                                                                              \
+        const int r_ = min((wm + 2 * (TMX)) * 32 + (IT) * 8 + (lane >> 3), rows - 1);              \
+        const size_t o_ = (size_t)(row0 + r_) * g.N + n0 + wn * 64 + (lane & 7) * 8;               \
+        av##IT = *reinterpret_cast<const uint4*>(g.aux_a + o_);                                    \
+        bv##IT = *reinterpret_cast<const uint4*>(g.aux_b + o_);                                    \
+    }
+#define UNIPOOL_LOAD_AB(TMX)                                                                       \
+    UNIPOOL_LOAD_AB1(TMX, 0) UNIPOOL_LOAD_AB1(TMX, 1) UNIPOOL_LOAD_AB1(TMX, 2) UNIPOOL_LOAD_AB1(TMX, 3)
+        if constexpr (EPI == EPI_SWIGLU_BWD && MTV > 0) {
+            if (cols_ok) { UNIPOOL_LOAD_AB(0) }
+        }
 #pragma unroll
         for (int tm = 0; tm < MTV; tm++) {
             const int strip0 = (wm + 2 * tm) * 32;     // first row of the strip inside the tile
-            const int r_in = strip0 + lrow;
             // -- registers -> staging rows
             if constexpr (EPI == EPI_STORE) {
 #pragma unroll
@@ -493,22 +583,31 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
                     *reinterpret_cast<uint2*>(stg + lrow * SROW + (64 + c) * 2) = pack4(h[0], h[1], h[2], h[3]);
                 }
             } else {   // EPI_SWIGLU_BWD
-                const bool rok = r_in < rows;
-                const size_t grow = (size_t)(row0 + (rok ? r_in : 0));
+                if (cols_ok) {
+                    const int so = (lane >> 3) * AROW + (lane & 7) * 16;
+                    *reinterpret_cast<uint4*>(stga + so) = av0;
+                    *reinterpret_cast<uint4*>(stgb + so) = bv0;
+                    *reinterpret_cast<uint4*>(stga + so + 8 * AROW) = av1;
+                    *reinterpret_cast<uint4*>(stgb + so + 8 * AROW) = bv1;
+                    *reinterpret_cast<uint4*>(stga + so + 16 * AROW) = av2;
+                    *reinterpret_cast<uint4*>(stgb + so + 16 * AROW) = bv2;
+                    *reinterpret_cast<uint4*>(stga + so + 24 * AROW) = av3;
+                    *reinterpret_cast<uint4*>(stgb + so + 24 * AROW) = bv3;
+                    if (tm + 1 < MTV) { UNIPOOL_LOAD_AB(tm + 1) }
+                }
 #pragma unroll
                 for (int tn = 0; tn < TN; tn++)
 #pragma unroll
                     for (int q = 0; q < 4; q++) {
                         const int c = tn * 32 + 8 * q + 4 * lhalf;     // column inside the wave's 64
-                        const int col = n0 + wn * 64 + c;
                         float da[4] = {0.f, 0.f, 0.f, 0.f}, db[4] = {0.f, 0.f, 0.f, 0.f};
-                        if (rok && col < g.N) {
-                            union { uint2 u; bf16 h[4]; } av, bv;
-                            av.u = *reinterpret_cast<const uint2*>(g.aux_a + grow * g.N + col);
-                            bv.u = *reinterpret_cast<const uint2*>(g.aux_b + grow * g.N + col);
+                        if (cols_ok) {
+                            union { uint2 u; bf16 h[4]; } a4, b4;
+                            a4.u = *reinterpret_cast<const uint2*>(stga + lrow * AROW + c * 2);
+                            b4.u = *reinterpret_cast<const uint2*>(stgb + lrow * AROW + c * 2);
 #pragma unroll
                             for (int i = 0; i < 4; i++) {
-                                const float a = (float)av.h[i], b = (float)bv.h[i];
+                                const float a = (float)a4.h[i], b = (float)b4.h[i];
                                 const float dh = acc[tm][tn][4 * q + i];
                                 const float sg = logistic_f(a);
                                 da[i] = dh * b * sg * (1.0f + a * (1.0f - sg));
@@ -562,6 +661,10 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
             }
         }
     }
+    PHASE_STAMP(t_end);
+    PHASE_COMMIT(t_begin, t_filled, t_looped, t_end);
+#undef UNIPOOL_LOAD_AB
+#undef UNIPOOL_LOAD_AB1
 }
 
 template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL>
@@ -582,13 +685,18 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
     const int lt_end = min(total, (xcd + 1) * per_xcd);
     int32_t* counter = g.tile_meta + kSchedBase + g.launch_slot * kNumXcd + xcd;
     const int wm = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8);        // wavefronts 4..7: odd strips
+    // The counter is read one tile ahead: the number of the next tile is requested when a tile
+    // starts and has long arrived when the tile ends, so the round trip of the atomic is off the path.
+    int ticket = 0;
+    if (threadIdx.x == 0) ticket = atomicAdd(counter, 1);
     for (;;) {
         __syncthreads();              // the previous tile's staging space is free
-        if (threadIdx.x == 0) *reinterpret_cast<volatile int*>(smem) = atomicAdd(counter, 1);
+        if (threadIdx.x == 0) *reinterpret_cast<volatile int*>(smem) = ticket;
         __syncthreads();
         const int lt = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(smem)) + xcd * per_xcd;
         __syncthreads();
         if (lt >= lt_end) break;
+        if (threadIdx.x == 0) ticket = atomicAdd(counter, 1);
         const int grp = lt / (G * g.n_tiles_n);
         const int rem = lt % (G * g.n_tiles_n);
         const int nt = rem / G;
@@ -739,18 +847,31 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
         const int a = i >> 2, b = i & 3;
         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pfr[buf][a], qfr[buf][b], acc[a][b], 0, 0, 0);
     };
+    // ISSUE: the loads of K block kb-1+NS go out during this stage, into the buffer that stage kb-1
+    // has released, one every other MFMA (a burst of loads would stall the wavefronts, MFMAs included,
+    // for as long as the address unit's queue takes to drain).
     auto stage_body = [&](auto issue_c, int kb) {
         constexpr bool ISSUE = decltype(issue_c)::value;
         const int stage = kb % NS;
+        if constexpr (ISSUE) next_block();
+        static_assert(LPS * (KS - 1) * 2 <= 16 * (KS - 1) && KS >= 2, "one load per two MFMA slots");
 #pragma unroll
         for (int ks = 0; ks < KS - 1; ks++) {
 #pragma unroll
             for (int i = 0; i < 16; i++) {
                 mfma_one(ks & 1, i);
                 if (i < 8) frag_load(stage, ks + 1, (ks + 1) & 1, i);
+                if constexpr (ISSUE) {
+                    constexpr int SL = 16 * (KS - 1);
+                    const int slot = ks * 16 + i;
+#pragma unroll
+                    for (int u = 0; u < LPS; u++)
+                        if (u * SL / LPS == slot) issue_one((kb + NS - 1) % NS, u);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if constexpr (ISSUE) ld_r += BK;
         constexpr int buf = (KS - 1) & 1;
 #pragma unroll
         for (int i = 0; i < 4; i++) mfma_one(buf, i);
@@ -758,17 +879,13 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
         if (nb - 2 - kb >= NS - 2) wait_vmcnt<(NS - 2) * LPS>();
         else wait_vmcnt<0>();
         __syncthreads();
-        if constexpr (ISSUE) next_block();
 #pragma unroll
         for (int i = 0; i < 12; i++) {
             mfma_one(buf, 4 + i);
-            if (ISSUE && i < LPS) issue_one(stage, i);
             if (i < 8) frag_load((kb + 1) % NS, 0, 0, i);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if constexpr (ISSUE) ld_r += BK;
     };
-    static_assert(LPS <= 12, "load issue is spread over the last 12 MFMAs of a stage");
 #pragma unroll
     for (int s = 0; s < NS; s++)
         if (s < nb) {
@@ -783,8 +900,9 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
 #pragma unroll
     for (int j = 0; j < 8; j++) frag_load(0, 0, 0, j);
     {
-        int kb = 0;
-        for (; kb + NS < nb; kb++) stage_body(std::integral_constant<bool, true>{}, kb);
+        stage_body(std::integral_constant<bool, false>{}, 0);       // nb >= 1 here
+        int kb = 1;
+        for (; kb - 1 + NS < nb; kb++) stage_body(std::integral_constant<bool, true>{}, kb);
         for (; kb < nb; kb++) stage_body(std::integral_constant<bool, false>{}, kb);
     }
 
@@ -1021,3 +1139,13 @@ hipError_t mfma_route_bwd_mm(const unipool_shape& s, const void* x, const void* 
 }
 
 }  // namespace unipool
+
+#ifdef UNIPOOL_PHASE_TIMES
+// Copies the phase sums to the host ([1024][8] values) and clears them.
+extern "C" int unipool_debug_phase_times(unsigned long long* out) {
+    hipError_t e = hipMemcpyFromSymbol(out, HIP_SYMBOL(unipool::g_phase_times), sizeof(unsigned long long) * 8192);
+    if (e != hipSuccess) return (int)e;
+    static unsigned long long zeros[8192];
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(unipool::g_phase_times), zeros, sizeof(zeros));
+}
+#endif
