@@ -102,6 +102,13 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+// Workgroup barrier that orders LDS traffic only: earlier LDS operations of the wavefront are
+// complete, outstanding global stores and loads are left in flight (__syncthreads() would wait for
+// every global store the compiler knows of, i.e. for the whole epilogue of a tile to reach memory).
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ unsigned lds_addr_of(const void* p) {
     return (unsigned)(size_t)(__attribute__((address_space(3))) const char*)p;
 }
@@ -450,7 +457,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
 #ifdef UNIPOOL_PHASE_TIMES
         PHASE_CLOCK(c1_);
 #endif
-        __syncthreads();
+        lds_barrier();
 #ifdef UNIPOOL_PHASE_TIMES
         PHASE_CLOCK(c2_);
         acc_wait_ += c1_ - c0_;
@@ -480,7 +487,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     // batch of stage 1, which may be shorter than XI loads, then has landed too: stricter than needed)
     if (nk >= NSW) wait_vmcnt<(NSW - 1) * WI>();
     else wait_vmcnt<0>();
-    __syncthreads();
+    lds_barrier();
     PHASE_STAMP(t_filled);
 #ifdef UNIPOOL_PHASE_TIMES
     PHASE_CLOCK(cl0_);
@@ -497,7 +504,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
         for (; kt + 1 < nk; kt++) stage_body(T{}, F{}, kt);
         for (; kt < nk; kt++) stage_body(F{}, F{}, kt);
     }
-    __syncthreads();   // every wavefront is done with the operand tiles: LDS becomes staging space
+    lds_barrier();   // every wavefront is done with the operand tiles: LDS becomes staging space
     PHASE_STAMP(t_looped);
 #ifdef UNIPOOL_PHASE_TIMES
     PHASE_CLOCK(cl1_);
@@ -690,11 +697,11 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
     int ticket = 0;
     if (threadIdx.x == 0) ticket = atomicAdd(counter, 1);
     for (;;) {
-        __syncthreads();              // the previous tile's staging space is free
+        lds_barrier();                // the previous tile's staging space is free
         if (threadIdx.x == 0) *reinterpret_cast<volatile int*>(smem) = ticket;
-        __syncthreads();
+        lds_barrier();
         const int lt = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(smem)) + xcd * per_xcd;
-        __syncthreads();
+        lds_barrier();
         if (lt >= lt_end) break;
         if (threadIdx.x == 0) ticket = atomicAdd(counter, 1);
         const int grp = lt / (G * g.n_tiles_n);
