@@ -8,7 +8,8 @@
 //              possibly chained over several layers; weight gradients)
 //
 // Common structure
-//   * 256 threads = 4 wavefronts, one workgroup per CU, accumulators in the upper register file.
+//   * One workgroup per CU: 8 wavefronts (gemm_xw) or 4 with the accumulators in the upper register
+//     file (gemm_ptq).
 //   * Operand tiles go global -> LDS directly (global_load_lds_dwordx4), NS stages deep, one
 //     barrier per K step.  The loads are issued through inline assembly so that the wait counts
 //     are ours: the compiler would otherwise wait for every outstanding load before any LDS read.
@@ -20,8 +21,9 @@
 //     lane ends up with four consecutive output columns of one row: results are staged through
 //     LDS and leave the CU as 16-byte row segments.
 //   * Row groups come from a device-side tile table; nothing is read back to the host.  Tiles are
-//     walked in an order that keeps the tiles of one expert on one XCD (workgroup ids are dealt
-//     round-robin to the 8 XCDs, each of which has its own L2).
+//     walked in a fixed order that keeps the tiles of one expert on one XCD (workgroup ids are dealt
+//     round-robin to the 8 XCDs, each of which has its own L2) and lets a workgroup request the first
+//     stages of its next tile before the epilogue of the current one.
 #include <type_traits>
 
 #include "kernels.h"
@@ -163,8 +165,8 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// tile table: [0] = number of row tiles; [16 .. 48) = tile counters of up to four launches (one per
-// XCD each), zeroed here; entry i at kTileBase + 4i: expert, first row, rows in tile
+// tile table: [0] = number of row tiles; [16 .. 48) = spare words, zeroed here; entry i at
+// kTileBase + 4i: expert, first row, rows in tile
 // ---------------------------------------------------------------------------------------------
 constexpr int kTileBase = 64;
 constexpr int kSchedBase = 16;
@@ -172,7 +174,9 @@ constexpr int kSchedBase = 16;
 __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restrict__ offsets, int E,
                                                           int total_rows, int BM,
                                                           int32_t* __restrict__ meta) {
-    __shared__ int first[kMaxE + 1];      // exclusive prefix sum of tiles per expert
+    __shared__ int lrows[512];            // rows per expert (0 past E)
+    __shared__ int lkey[512];             // place of an expert in the dealt order (a permutation)
+    __shared__ int ltiles[512];           // tiles of the expert at a given place
     __shared__ int scan[2][512];
     const int t = threadIdx.x;
     int r0 = 0, r1 = 0;
@@ -181,8 +185,30 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
         r1 = offsets ? offsets[t + 1] : total_rows;
     }
     const int nt = (r1 - r0 + BM - 1) / BM;
-    // inclusive Hillis-Steele scan over 512 entries
-    scan[0][t] = nt;
+    lrows[t] = r1 - r0;
+    __syncthreads();
+    // Order of the experts in the tile list.  The persistent workgroups walk the list in a fixed
+    // pattern (one eighth of it per XCD, dealt in rounds to the workgroups of the XCD), so the list
+    // is laid out for them: experts sorted by rows, descending, are dealt to the eight parts in
+    // serpentine order (0..7, 7..0, ...), which gives every XCD the same amount of work to within
+    // one small expert and makes the tiles that run at the same time equally long.
+    int rank = 0;                         // experts with more rows (ties: lower index first)
+    for (int o = 0; o < 512; o++) {
+        const int ro = lrows[o], rt = r1 - r0;
+        rank += (ro > rt) || (ro == rt && o < t);
+    }
+    const int lap = rank / kNumXcd, posn = rank % kNumXcd;
+    const int part = (lap & 1) ? kNumXcd - 1 - posn : posn;
+    const int place = part * (512 / kNumXcd) + lap;     // unique: lap < 64
+    lkey[t] = place;
+    __syncthreads();
+    int dense = 0;                        // experts placed before this one
+    for (int o = 0; o < 512; o++) dense += lkey[o] < place;
+    ltiles[dense] = nt;
+    __syncthreads();
+    // exclusive prefix sum of the tiles in list order (inclusive Hillis-Steele scan over 512 entries)
+    const int mine = ltiles[t];
+    scan[0][t] = mine;
     __syncthreads();
     int cur = 0;
     for (int d = 1; d < 512; d <<= 1) {
@@ -190,17 +216,15 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
         cur ^= 1;
         __syncthreads();
     }
-    const int my_first = scan[cur][t] - nt;
-    if (t < E) first[t] = my_first;
-    if (t == 0) {
-        first[E] = scan[cur][511];
-        meta[0] = scan[cur][511];
-    }
+    ltiles[t] = scan[cur][t] - mine;      // first tile of the expert at place t
+    if (t == 0) meta[0] = scan[cur][511];
     if (t >= kSchedBase && t < kSchedBase + 4 * kNumXcd) meta[t] = 0;
+    __syncthreads();
     // The rows of an expert are cut into equal tiles (multiples of 32 rows) rather than into full
     // tiles plus a remainder: tiles that share an expert's weights then take equally long and stay
     // in step, so the second reader of a weight tile still finds it in L2.
     if (t < E) {
+        const int my_first = ltiles[dense];
         const int per = nt > 0 ? (((r1 - r0 + nt - 1) / nt + 31) / 32) * 32 : 0;
         for (int i = 0; i < nt; i++) {
             int32_t* m = meta + kTileBase + 4 * (my_first + i);
@@ -236,9 +260,28 @@ __global__ void build_tiles_flat_kernel(int total_rows, int BM, int32_t* __restr
 constexpr int kXwWaves = 8;
 constexpr int kXwThreads = kXwWaves * 64;
 
+struct TileRef {
+    int valid, expert, row0, rows, nt;
+};
+
+// Wavefronts that share one staging region of 32 KiB in the epilogue, per epilogue kind: the staging
+// areas live in the operand buffers the last stage has released.  Kinds whose eight areas fit two
+// regions leave a third buffer free, which then takes the next tile's W(1) ahead of time.
+template <int EPI> struct Staging {
+    static constexpr int SC = EPI == EPI_SWIGLU_FWD ? 96 : 64;   // columns per staging row
+    static constexpr int SROW = SC * 2 + 16;                    // row stride in bytes
+    static constexpr int WSTG = (EPI == EPI_SWIGLU_BWD ? 2 : 1) * 32 * SROW;   // bytes per wavefront
+    static constexpr int RW = 32768 / WSTG < kXwWaves ? 32768 / WSTG : kXwWaves;
+    static constexpr int REGIONS = EPI == EPI_F32 ? 0 : (kXwWaves + RW - 1) / RW;
+    static constexpr bool PREW1 = REGIONS <= 2;
+    static_assert(REGIONS <= 3, "three operand buffers are free in the epilogue");
+};
+
+// pre: what the previous tile has already requested for this one (bit 0: X(0) and W(0), bit 1: W(1));
+// g0: number of K stages this workgroup has run before this tile (the LDS buffers rotate on).
 template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL, int MTV>
-__device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int expert, int row0, int rows,
-                                        int nt) {
+__device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef cur, TileRef nxt, int pre,
+                                        int g0) {
     constexpr int NW = kXwWaves;
     constexpr int TN = 2;
     constexpr int XBYTES = BM * BK * 2;
@@ -258,11 +301,13 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     // direct-to-LDS pipeline.  Making the inputs opaque here keeps every body self-contained.
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
-    expert = __builtin_amdgcn_readfirstlane(expert);
-    row0 = __builtin_amdgcn_readfirstlane(row0);
-    rows = __builtin_amdgcn_readfirstlane(rows);
-    nt = __builtin_amdgcn_readfirstlane(nt);
-    asm volatile("" : "+s"(expert), "+s"(row0), "+s"(rows), "+s"(nt));
+    int expert = __builtin_amdgcn_readfirstlane(cur.expert);
+    int row0 = __builtin_amdgcn_readfirstlane(cur.row0);
+    int rows = __builtin_amdgcn_readfirstlane(cur.rows);
+    int nt = __builtin_amdgcn_readfirstlane(cur.nt);
+    pre = __builtin_amdgcn_readfirstlane(pre);
+    g0 = __builtin_amdgcn_readfirstlane(g0);
+    asm volatile("" : "+s"(expert), "+s"(row0), "+s"(rows), "+s"(nt), "+s"(pre), "+s"(g0));
     PHASE_STAMP(t_begin);
 #ifdef UNIPOOL_PHASE_TIMES
     long long acc_wait_ = 0, acc_bar_ = 0, acc_cyc_ = 0;
@@ -271,54 +316,56 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave & 3, wm = wave >> 2;
     const unsigned lds0 = lds_addr_of(smem);
-    const bf16* We = g.W + (long long)expert * g.w_stride;
     const int n0 = nt * BN;                 // first column of the tile (plain epilogues)
     const int f0 = nt * (BN / 2);           // first column per half (SWIGLU_FWD)
-    const int strips = (rows + 31) >> 5;    // strips of the tile that hold rows
 
     // ---- per-lane source pointers of the direct-to-LDS loads ----------------------------------
     // Load i of a wavefront fills LDS chunks (i*NW + wave)*64 .. +63: 8 rows of 128 bytes.  Loads
     // whose rows lie in strips without rows are left out (xload[i] false, wave-uniform).
     const char* xsrc[XI];
     bool xload[XI];
-#pragma unroll
-    for (int i = 0; i < XI; i++) {
-        const int q = (i * NW + wave) * 64 + lane;
-        const int row = q / XT::CPR;
-        const int cc = (q % XT::CPR) ^ XT::swz(row);
-        const int grow = row0 + min(row, rows - 1);
-        xsrc[i] = reinterpret_cast<const char*>(g.X + (size_t)grow * g.ldx + cc * 8);
-        xload[i] = ((i * NW + wave) * 64 / XT::CPR) < strips * 32;
-    }
     const char* wsrc[WI];
-    size_t wstep;                           // bytes per K step
-    if constexpr (WK) {
+    const size_t wstep = WK ? (size_t)BK * 2 : (size_t)BK * g.ldw * 2;      // bytes per K step
+    auto set_sources = [&](int t_expert, int t_row0, int t_rows, int t_nt) {
+        const bf16* We = g.W + (long long)t_expert * g.w_stride;
+        const int t_n0 = t_nt * BN, t_f0 = t_nt * (BN / 2);
+        const int t_strips = (t_rows + 31) >> 5;
 #pragma unroll
-        for (int i = 0; i < WI; i++) {
+        for (int i = 0; i < XI; i++) {
             const int q = (i * NW + wave) * 64 + lane;
-            const int row = q / WTK::CPR;
-            const int cc = (q % WTK::CPR) ^ WTK::swz(row);
-            int wrow;
-            if constexpr (EPI == EPI_SWIGLU_FWD) {
-                const int half = row / (BN / 2);
-                wrow = half * g.up_rows + min(f0 + row % (BN / 2), g.N - 1);
-            } else {
-                wrow = min(n0 + row, g.N - 1);
+            const int row = q / XT::CPR;
+            const int cc = (q % XT::CPR) ^ XT::swz(row);
+            const int grow = t_row0 + min(row, t_rows - 1);
+            xsrc[i] = reinterpret_cast<const char*>(g.X + (size_t)grow * g.ldx + cc * 8);
+            xload[i] = ((i * NW + wave) * 64 / XT::CPR) < t_strips * 32;
+        }
+        if constexpr (WK) {
+#pragma unroll
+            for (int i = 0; i < WI; i++) {
+                const int q = (i * NW + wave) * 64 + lane;
+                const int row = q / WTK::CPR;
+                const int cc = (q % WTK::CPR) ^ WTK::swz(row);
+                int wrow;
+                if constexpr (EPI == EPI_SWIGLU_FWD) {
+                    const int half = row / (BN / 2);
+                    wrow = half * g.up_rows + min(t_f0 + row % (BN / 2), g.N - 1);
+                } else {
+                    wrow = min(t_n0 + row, g.N - 1);
+                }
+                wsrc[i] = reinterpret_cast<const char*>(We + (size_t)wrow * g.ldw + cc * 8);
             }
-            wsrc[i] = reinterpret_cast<const char*>(We + (size_t)wrow * g.ldw + cc * 8);
-        }
-        wstep = (size_t)BK * 2;
-    } else {
+        } else {
 #pragma unroll
-        for (int i = 0; i < WI; i++) {
-            const int q = (i * NW + wave) * 64 + lane;
-            const int krow = q / WTN::CPR;
-            const int cc = (q % WTN::CPR) ^ WTN::swz(krow);
-            const int col = min(n0 + cc * 8, g.N - 8);
-            wsrc[i] = reinterpret_cast<const char*>(We + (size_t)krow * g.ldw + col);
+            for (int i = 0; i < WI; i++) {
+                const int q = (i * NW + wave) * 64 + lane;
+                const int krow = q / WTN::CPR;
+                const int cc = (q % WTN::CPR) ^ WTN::swz(krow);
+                const int col = min(t_n0 + cc * 8, g.N - 8);
+                wsrc[i] = reinterpret_cast<const char*>(We + (size_t)krow * g.ldw + col);
+            }
         }
-        wstep = (size_t)BK * g.ldw * 2;
-    }
+    };
+    set_sources(expert, row0, rows, nt);
 
     f32x16 acc[MTV > 0 ? MTV : 1][TN];
 #pragma unroll
@@ -352,18 +399,25 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
     // spread between the MFMAs.
     constexpr int NSX = NS, NSW = NS + 1;
     constexpr int WBASE = NSX * XBYTES;
+    static_assert(NSX == 2 && NSW == 3, "buffer rotation and wait counts below");
+    // Stage kt of this tile lives in X buffer (g0 + kt) mod 2 and W buffer (g0 + kt) mod 3: the
+    // buffers rotate on from tile to tile, so the first stages of the next tile can be requested
+    // while this tile's last stage and epilogue still hold theirs.
+    const int x0 = g0 & 1, w0 = g0 % 3;
+    auto xbuf = [&](int kt) { return (kt + x0) & 1; };
+    auto wbuf = [&](int kt) { return (kt + w0) % 3; };
     bf16x8 wfr[2][TN], xfr[2][MTV > 0 ? MTV : 1];
     constexpr int NM = MTV * TN;                    // MFMAs per slice
     constexpr int NL = MTV > 0 ? MTV + TN : 0;      // fragments per slice
     auto frag_load = [&](int kt, int ks, int buf, int j) {
         if (j < TN) {
-            const char* wb = smem + WBASE + (kt % NSW) * WBYTES;
+            const char* wb = smem + WBASE + wbuf(kt) * WBYTES;
             if constexpr (WK)
                 wfr[buf][j] = lds_read16(wb + WTK::off(wpos[j] + (lane & 31), ks * 2 + (lane >> 5)));
             else
                 wfr[buf][j] = WTN::frag(wb, ks, wpos[j], lane);
         } else {
-            const char* xb = smem + (kt % NSX) * XBYTES;
+            const char* xb = smem + xbuf(kt) * XBYTES;
             const int strip = wm + 2 * (j - TN);
             xfr[buf][j - TN] = lds_read16(xb + XT::off(strip * 32 + (lane & 31), ks * 2 + (lane >> 5)));
         }
@@ -384,18 +438,19 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
 #pragma unroll
         for (int i = 0; i < WI; i++) wk[i] = ((i * NW + wave) * 64 + lane) / WTN::CPR;
     }
-    auto issue_x = [&](int kt, int i) {
+    // load i of stage kt of the tile the sources point at, into the buffer of stage kb of this tile
+    auto issue_x = [&](int kt, int i, int kb) {
         if (!xload[i]) return;
         const char* src = xsrc[i] + (size_t)kt * BK * 2;
         if constexpr (KTAIL)
             if (kt * BK + xk[i] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
-        glds16(src, lds0 + (kt % NSX) * XBYTES + ((i * NW + wave) * 64) * 16);
+        glds16(src, lds0 + xbuf(kb) * XBYTES + ((i * NW + wave) * 64) * 16);
     };
-    auto issue_w = [&](int kt, int i) {
+    auto issue_w = [&](int kt, int i, int kb) {
         const char* src = wsrc[i] + (size_t)kt * wstep;
         if constexpr (KTAIL)
             if (kt * BK + wk[i] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
-        glds16(src, lds0 + WBASE + (kt % NSW) * WBYTES + ((i * NW + wave) * 64) * 16);
+        glds16(src, lds0 + WBASE + wbuf(kb) * WBYTES + ((i * NW + wave) * 64) * 16);
     };
     // One stage.  IX / IW: the loads of X(kt+1) / W(kt+2) go out during this stage, into the buffers
     // that stage kt-1 has released.  They are spread over the slices before the meeting point, X in
@@ -410,11 +465,11 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
         if constexpr (SL == 0) {
             if constexpr (IX) {
 #pragma unroll
-                for (int u = 0; u < XI; u++) issue_x(kt + 1, u);
+                for (int u = 0; u < XI; u++) issue_x(kt + 1, u, kt + 1);
             }
             if constexpr (IW) {
 #pragma unroll
-                for (int u = 0; u < WI; u++) issue_w(kt + 2, u);
+                for (int u = 0; u < WI; u++) issue_w(kt + 2, u, kt + 2);
             }
         }
 #pragma unroll
@@ -428,12 +483,12 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
                 if constexpr (IX) {
 #pragma unroll
                     for (int u = 0; u < XI; u++)
-                        if (u * H / XI == slot) issue_x(kt + 1, u);
+                        if (u * H / XI == slot) issue_x(kt + 1, u, kt + 1);
                 }
                 if constexpr (IW) {
 #pragma unroll
                     for (int u = 0; u < WI; u++)
-                        if (H + u * (SL - H) / WI == slot) issue_w(kt + 2, u);
+                        if (H + u * (SL - H) / WI == slot) issue_w(kt + 2, u, kt + 2);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -449,11 +504,8 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
 #ifdef UNIPOOL_PHASE_TIMES
         PHASE_CLOCK(c0_);
 #endif
-        {
-            static_assert(NSX == 2 && NSW == 3, "wait counts below");
-            if (nk - 2 - kt >= 1) wait_vmcnt<WI>();
-            else wait_vmcnt<0>();
-        }
+        if (nk - 2 - kt >= 1) wait_vmcnt<WI>();
+        else wait_vmcnt<0>();
 #ifdef UNIPOOL_PHASE_TIMES
         PHASE_CLOCK(c1_);
 #endif
@@ -471,17 +523,24 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // prologue: X(0) W(0) X(1) W(1) W(2)
+    // prologue: X(0) W(0) X(1) W(1) W(2), less what the previous tile has requested already
+    if (!(pre & 1)) {
 #pragma unroll
-    for (int s = 0; s < NSW; s++) {
-        if (s < NSX && s < nk) {
+        for (int i = 0; i < XI; i++) issue_x(0, i, 0);
 #pragma unroll
-            for (int i = 0; i < XI; i++) issue_x(s, i);
+        for (int i = 0; i < WI; i++) issue_w(0, i, 0);
+    }
+    if (nk > 1) {
+#pragma unroll
+        for (int i = 0; i < XI; i++) issue_x(1, i, 1);
+        if (!(pre & 2)) {
+#pragma unroll
+            for (int i = 0; i < WI; i++) issue_w(1, i, 1);
         }
-        if (s < nk) {
+    }
+    if (nk > 2) {
 #pragma unroll
-            for (int i = 0; i < WI; i++) issue_w(s, i);
-        }
+        for (int i = 0; i < WI; i++) issue_w(2, i, 2);
     }
     // stage 0 has landed when at most the two W batches of stages 1 and 2 are outstanding (the X
     // batch of stage 1, which may be shorter than XI loads, then has landed too: stricter than needed)
@@ -504,8 +563,24 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
         for (; kt + 1 < nk; kt++) stage_body(T{}, F{}, kt);
         for (; kt < nk; kt++) stage_body(F{}, F{}, kt);
     }
-    lds_barrier();   // every wavefront is done with the operand tiles: LDS becomes staging space
+    lds_barrier();   // every wavefront is done with the operand tiles
     PHASE_STAMP(t_looped);
+    // The buffers of the last stage become the staging space of the epilogue; the others take the
+    // first stages of the next tile now, so that its pipeline is full when the epilogue ends.
+    constexpr bool PREW1 = Staging<EPI>::PREW1;
+    if constexpr (!KTAIL) {
+        if (nxt.valid) {
+            set_sources(nxt.expert, nxt.row0, nxt.rows, nxt.nt);
+#pragma unroll
+            for (int i = 0; i < XI; i++) issue_x(0, i, nk);
+#pragma unroll
+            for (int i = 0; i < WI; i++) issue_w(0, i, nk);
+            if (PREW1 && nk > 1) {
+#pragma unroll
+                for (int i = 0; i < WI; i++) issue_w(1, i, nk + 1);
+            }
+        }
+    }
 #ifdef UNIPOOL_PHASE_TIMES
     PHASE_CLOCK(cl1_);
     acc_cyc_ = cl1_ - cl0_;
@@ -533,18 +608,21 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
             }
         }
     } else {
-        constexpr int SC = (EPI == EPI_SWIGLU_FWD) ? 96 : (EPI == EPI_SWIGLU_BWD ? 128 : 64);
-        constexpr int SROW = SC * 2 + 16;              // staging row stride in bytes
-        constexpr int CPRS = SC / 8;                   // 16-byte chunks per staging row
-        // SWIGLU_BWD also stages the saved activations A and B of a strip: they are fetched as whole
-        // 128-byte row segments (one request per cache line instead of one per 16 bytes in the
-        // accumulator layout), a strip ahead, and picked up from LDS in the accumulator layout.
-        constexpr int AROW = 64 * 2 + 16;               // A / B staging row stride in bytes
-        constexpr int WSTG = 32 * SROW + (EPI == EPI_SWIGLU_BWD ? 2 * 32 * AROW : 0);
-        static_assert(kXwWaves * WSTG <= NSX * XBYTES + NSW * WBYTES, "staging fits the operand buffers");
-        char* stg = smem + wave * WSTG;
-        [[maybe_unused]] char* stga = stg + 32 * SROW;
-        [[maybe_unused]] char* stgb = stga + 32 * AROW;
+        using SG = Staging<EPI>;
+        constexpr int SROW = SG::SROW;                  // staging row stride in bytes
+        constexpr int CPRS = SG::SC / 8;                // 16-byte chunks per staging row
+        // Staging area of this wavefront: region 0 is the X buffer of the last stage, region 1 its W
+        // buffer, region 2 (SwiGLU backward only) the W buffer that would otherwise hold W(1) of the
+        // next tile.
+        const int region = wave / SG::RW;
+        const int rbase = region == 0 ? xbuf(nk - 1) * XBYTES
+                                      : WBASE + (region == 1 ? wbuf(nk - 1) : wbuf(nk + 1)) * WBYTES;
+        char* stg = smem + rbase + (wave % SG::RW) * SG::WSTG;
+        // SWIGLU_BWD stages the saved activations A and B of a strip in two areas of 32 x 64 values:
+        // they are fetched as whole 128-byte row segments (one request per cache line instead of one
+        // per 16 bytes in the accumulator layout), a strip ahead, picked up from LDS in the
+        // accumulator layout, and replaced in place by dA and dB, which leave as row segments again.
+        [[maybe_unused]] char* stgb = stg + 32 * SROW;
         [[maybe_unused]] uint4 av0, av1, av2, av3, bv0, bv1, bv2, bv3;
         // the 64 columns of a wavefront are inside N or outside as a whole (N is a multiple of 64)
         [[maybe_unused]] const bool cols_ok = n0 + wn * 64 < g.N;
@@ -591,15 +669,15 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
                 }
             } else {   // EPI_SWIGLU_BWD
                 if (cols_ok) {
-                    const int so = (lane >> 3) * AROW + (lane & 7) * 16;
-                    *reinterpret_cast<uint4*>(stga + so) = av0;
+                    const int so = (lane >> 3) * SROW + (lane & 7) * 16;
+                    *reinterpret_cast<uint4*>(stg + so) = av0;
                     *reinterpret_cast<uint4*>(stgb + so) = bv0;
-                    *reinterpret_cast<uint4*>(stga + so + 8 * AROW) = av1;
-                    *reinterpret_cast<uint4*>(stgb + so + 8 * AROW) = bv1;
-                    *reinterpret_cast<uint4*>(stga + so + 16 * AROW) = av2;
-                    *reinterpret_cast<uint4*>(stgb + so + 16 * AROW) = bv2;
-                    *reinterpret_cast<uint4*>(stga + so + 24 * AROW) = av3;
-                    *reinterpret_cast<uint4*>(stgb + so + 24 * AROW) = bv3;
+                    *reinterpret_cast<uint4*>(stg + so + 8 * SROW) = av1;
+                    *reinterpret_cast<uint4*>(stgb + so + 8 * SROW) = bv1;
+                    *reinterpret_cast<uint4*>(stg + so + 16 * SROW) = av2;
+                    *reinterpret_cast<uint4*>(stgb + so + 16 * SROW) = bv2;
+                    *reinterpret_cast<uint4*>(stg + so + 24 * SROW) = av3;
+                    *reinterpret_cast<uint4*>(stgb + so + 24 * SROW) = bv3;
                     if (tm + 1 < MTV) { UNIPOOL_LOAD_AB(tm + 1) }
                 }
 #pragma unroll
@@ -608,10 +686,13 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
                     for (int q = 0; q < 4; q++) {
                         const int c = tn * 32 + 8 * q + 4 * lhalf;     // column inside the wave's 64
                         float da[4] = {0.f, 0.f, 0.f, 0.f}, db[4] = {0.f, 0.f, 0.f, 0.f};
+                        // a lane overwrites exactly the eight bytes of A and of B it has read
+                        uint2* pa = reinterpret_cast<uint2*>(stg + lrow * SROW + c * 2);
+                        uint2* pb = reinterpret_cast<uint2*>(stgb + lrow * SROW + c * 2);
                         if (cols_ok) {
                             union { uint2 u; bf16 h[4]; } a4, b4;
-                            a4.u = *reinterpret_cast<const uint2*>(stga + lrow * AROW + c * 2);
-                            b4.u = *reinterpret_cast<const uint2*>(stgb + lrow * AROW + c * 2);
+                            a4.u = *pa;
+                            b4.u = *pb;
 #pragma unroll
                             for (int i = 0; i < 4; i++) {
                                 const float a = (float)a4.h[i], b = (float)b4.h[i];
@@ -621,21 +702,22 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
                                 db[i] = dh * a * sg;
                             }
                         }
-                        *reinterpret_cast<uint2*>(stg + lrow * SROW + c * 2) = pack4(da[0], da[1], da[2], da[3]);
-                        *reinterpret_cast<uint2*>(stg + lrow * SROW + (64 + c) * 2) = pack4(db[0], db[1], db[2], db[3]);
+                        *pa = pack4(da[0], da[1], da[2], da[3]);
+                        *pb = pack4(db[0], db[1], db[2], db[3]);
                     }
             }
             // -- staging rows -> global, 16 bytes per lane
+            constexpr int NCH = (EPI == EPI_SWIGLU_BWD ? 2 : 1) * CPRS;     // chunks per output row
 #pragma unroll
-            for (int it = 0; it < 32 * CPRS / 64; it++) {
+            for (int it = 0; it < 32 * NCH / 64; it++) {
                 const int id = it * 64 + lane;
-                const int srow = id / CPRS;
-                const int ch = id % CPRS;
+                const int srow = id / NCH;
+                const int ch = id % NCH;
                 const int rr = strip0 + srow;
                 if (rr >= rows) continue;
-                const uint4 v = *reinterpret_cast<const uint4*>(stg + srow * SROW + ch * 16);
                 const size_t grow = (size_t)(row0 + rr);
                 if constexpr (EPI == EPI_STORE) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(stg + srow * SROW + ch * 16);
                     const int col = n0 + wn * 64 + ch * 8;
                     if (col < g.N) {
                         bf16* dst = reinterpret_cast<bf16*>(g.out0) + grow * g.ldo + col;
@@ -651,6 +733,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
                         }
                     }
                 } else if constexpr (EPI == EPI_SWIGLU_FWD) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(stg + srow * SROW + ch * 16);
                     const int which = ch >> 2;
                     const int col = f0 + wn * 32 + (ch & 3) * 8;
                     if (col < g.N) {
@@ -659,6 +742,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, int exper
                     }
                 } else {
                     const int which = ch >> 3;
+                    const uint4 v = *reinterpret_cast<const uint4*>((which ? stgb : stg) + srow * SROW + (ch & 7) * 16);
                     const int col = n0 + wn * 64 + (ch & 7) * 8;
                     if (col < g.N) {
                         bf16* dst = reinterpret_cast<bf16*>(g.out0) + grow * g.ldo + which * g.N + col;
@@ -678,50 +762,68 @@ template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL>
 __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-    // ---- persistent workgroups -----------------------------------------------------------------
-    // One workgroup per CU stays resident and takes tiles from a counter.  (With one 160 KB
-    // workgroup per CU and tiles of unequal length, the in-order hardware dispatch leaves CUs idle.)
-    // Each XCD has its own L2, so the tile list is cut into eight contiguous parts and a
-    // workgroup takes tiles of the part of the XCD it runs on: the row tiles of an expert, which
-    // share the expert's weights, and its column tiles, which share its rows, stay on one L2.
+    // ---- persistent workgroups, static schedule ------------------------------------------------
+    // One workgroup per CU stays resident and walks a list of tiles that every wavefront can work
+    // out by itself (no counter, no hand-over through LDS), so the next tile is known while the
+    // current one runs and its first stages are requested before the epilogue.
+    //   * Workgroup b belongs to XCD b mod 8 (workgroups are dealt round-robin to the XCDs; if a
+    //     device dealt them otherwise, only the L2 locality below would suffer).  Each XCD has its own
+    //     L2, so the tile list is cut into eight contiguous parts: the row tiles of an expert, which
+    //     share the expert's weights, and its column tiles, which share its rows, stay on one L2.
+    //   * Inside a part, round n gives the next P tiles to the P workgroups of the XCD, rotated by n,
+    //     so that no workgroup keeps the same position inside the experts' tile groups.  The tile
+    //     table lists the experts of a part in descending order of rows: the workgroups of an XCD
+    //     work on tiles of nearly equal length at any time and end together.
     const int n_mt = g.tile_meta[0];
     const int G = g.group_m;
-    const int total = ((n_mt + G - 1) / G) * G * g.n_tiles_n;
+    const int per_group = G * g.n_tiles_n;
+    const int total = ((n_mt + G - 1) / G) * per_group;
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
-    const int xcd = __builtin_amdgcn_s_getreg((3 << 11) | 20) & (kNumXcd - 1);   // XCC_ID
+    const int xcd = blockIdx.x % kNumXcd;
+    const int slot = blockIdx.x / kNumXcd;
+    const int P = gridDim.x / kNumXcd;                 // workgroups per XCD (the grid is a multiple of 8)
     const int lt_end = min(total, (xcd + 1) * per_xcd);
-    int32_t* counter = g.tile_meta + kSchedBase + g.launch_slot * kNumXcd + xcd;
     const int wm = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8);        // wavefronts 4..7: odd strips
-    // The counter is read one tile ahead: the number of the next tile is requested when a tile
-    // starts and has long arrived when the tile ends, so the round trip of the atomic is off the path.
-    int ticket = 0;
-    if (threadIdx.x == 0) ticket = atomicAdd(counter, 1);
-    for (;;) {
-        lds_barrier();                // the previous tile's staging space is free
-        if (threadIdx.x == 0) *reinterpret_cast<volatile int*>(smem) = ticket;
-        lds_barrier();
-        const int lt = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(smem)) + xcd * per_xcd;
-        lds_barrier();
-        if (lt >= lt_end) break;
-        if (threadIdx.x == 0) ticket = atomicAdd(counter, 1);
-        const int grp = lt / (G * g.n_tiles_n);
-        const int rem = lt % (G * g.n_tiles_n);
-        const int nt = rem / G;
-        const int mt = grp * G + rem % G;
-        if (mt >= n_mt) continue;
-        const int expert = g.tile_meta[kTileBase + 4 * mt];
-        const int row0 = g.tile_meta[kTileBase + 4 * mt + 1];
-        const int rows = g.tile_meta[kTileBase + 4 * mt + 2];
-        if (rows <= 0) continue;
-        // strips wm, wm+2, ... of this wavefront that hold rows; every body runs the same barriers
-        const int strips = (rows + 31) >> 5;
-        switch (max(0, (strips - wm + 1) >> 1)) {
-            case 0: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 0>(g, smem, expert, row0, rows, nt); break;
-            case 1: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 1>(g, smem, expert, row0, rows, nt); break;
-            case 2: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 2>(g, smem, expert, row0, rows, nt); break;
-            case 3: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 3>(g, smem, expert, row0, rows, nt); break;
-            default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4>(g, smem, expert, row0, rows, nt); break;
+    int round = 0;
+    // the next tile of this workgroup that holds rows, or valid = 0 at the end of the list
+    auto next_tile = [&]() {
+        TileRef t = {0, 0, 0, 0, 0};
+        for (;;) {
+            const int lt = xcd * per_xcd + round * P + (slot + round) % P;
+            if (lt >= lt_end) return t;
+            round++;
+            const int grp = lt / per_group;
+            const int rem = lt % per_group;
+            const int mt = grp * G + rem % G;
+            if (mt >= n_mt) continue;
+            const int rows = g.tile_meta[kTileBase + 4 * mt + 2];
+            if (rows <= 0) continue;
+            t.valid = 1;
+            t.expert = g.tile_meta[kTileBase + 4 * mt];
+            t.row0 = g.tile_meta[kTileBase + 4 * mt + 1];
+            t.rows = rows;
+            t.nt = rem / G;
+            return t;
         }
+    };
+    const int nk = KTAIL ? (g.K + BK - 1) / BK : g.K / BK;
+    TileRef cur = next_tile();
+    int pre = 0, g0 = 0;
+    while (cur.valid) {
+        const TileRef nxt = next_tile();
+        // strips wm, wm+2, ... of this wavefront that hold rows; every body runs the same barriers
+        const int strips = (cur.rows + 31) >> 5;
+        switch (max(0, (strips - wm + 1) >> 1)) {
+            case 0: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 0>(g, smem, cur, nxt, pre, g0); break;
+            case 1: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 1>(g, smem, cur, nxt, pre, g0); break;
+            case 2: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 2>(g, smem, cur, nxt, pre, g0); break;
+            case 3: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 3>(g, smem, cur, nxt, pre, g0); break;
+            default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4>(g, smem, cur, nxt, pre, g0); break;
+        }
+        lds_barrier();                // the staging space is free: the next tile may load into it
+        pre = (!KTAIL && nxt.valid) ? ((Staging<EPI>::PREW1 && nk > 1) ? 3 : 1) : 0;
+        g0 = (g0 + nk) % 6;           // the buffers repeat with period 2 and 3
+        cur = nxt;
     }
 }
 
@@ -989,7 +1091,7 @@ hipError_t run_xw(GemmArgs a, int max_row_tiles, hipStream_t st) {
     }
     a.group_m = 2;
     (void)max_row_tiles;
-    const int grid = num_cus();
+    const int grid = max(kNumXcd, num_cus() / kNumXcd * kNumXcd);
     kern<<<grid, kXwThreads, kGemmLds, st>>>(a);
     return hipGetLastError();
 }
