@@ -73,7 +73,7 @@ struct GemmArgs {
     int K, N;             // reduction length; number of output columns (per half for SWIGLU_FWD)
     int n_tiles_n;
     int32_t* tile_meta;
-    int launch_slot;      // which of the table's tile counters this launch uses (0..3)
+    int launch_slot;      // ordinal of the launch inside its entry point (profiling builds file phase times by it)
     void* out0;
     void* out1;
     void* out2;
@@ -1062,6 +1062,7 @@ __global__ void reduce_partials_kernel(const float* __restrict__ part, int npart
 // ---------------------------------------------------------------------------------------------
 // launch helpers
 // ---------------------------------------------------------------------------------------------
+constexpr int kFlatBM = 128;
 constexpr int kBM = 256, kBN = 256, kBK = 64, kNS = 2;   // gemm_xw: 128-byte row segments per load
 constexpr int kPtqBK = 32, kPtqNS = 4;                      // gemm_ptq
 constexpr int kGemmLds = kNS * kBM * kBK * 2 + (kNS + 1) * kBN * kBK * 2;   // 2 X stages + 3 W stages = 160 KiB
@@ -1113,8 +1114,10 @@ hipError_t run_ptq(const PtqArgs& a, hipStream_t st) {
 
 hipError_t build_tiles(const int32_t* offsets, int E, int total_rows, int32_t* meta, hipStream_t st) {
     if (offsets == nullptr) {
-        const int n = cdiv(total_rows, kBM);
-        build_tiles_flat_kernel<<<cdiv(max(n, 64), 256), 256, 0, st>>>(total_rows, kBM, meta);
+        // ungrouped matrices (router): half-height tiles, so that a token count of 128 per CU already
+        // gives every CU a tile
+        const int n = cdiv(total_rows, kFlatBM);
+        build_tiles_flat_kernel<<<cdiv(max(n, 64), 256), 256, 0, st>>>(total_rows, kFlatBM, meta);
     } else {
         build_tiles_kernel<<<1, 512, 0, st>>>(offsets, E, total_rows, kBM, meta);
     }

@@ -11,53 +11,68 @@ constexpr int kVPL = kMaxE / kWave;       // logits per lane
 constexpr int kWavesPerBlock = 4;
 constexpr int kTokPerWave = kRouterTokensPerBlock / kWavesPerBlock;
 
-// Statistics and selection for the tokens of one block.  Partial sums leave the block in a
-// fixed order, so the final reduction over blocks is deterministic.
+// Statistics and selection for the tokens of one block.  A group of GS lanes owns one token at a
+// time (64 / GS tokens per wavefront in flight); lane s of the group holds the logits of experts
+// s, s + GS, ... (VPL of them, E <= GS * VPL).  Partial sums leave the block in a fixed order, so the
+// final reduction over blocks is deterministic.
+template <int GS, int VPL>
 __global__ __launch_bounds__(256) void route_score_topk_kernel(
     const float* __restrict__ logits, int T, int E, int k, float sigma_c, float eps,
     int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate,
     int32_t* __restrict__ cnt_part, float* __restrict__ psum_part) {
+    constexpr int TPW = 64 / GS;                       // tokens per wavefront at a time
+    static_assert(VPL <= 32 && kTokPerWave % TPW == 0, "taken-mask width; whole rounds per wavefront");
     __shared__ float lds_ps[kWavesPerBlock][kMaxE];
     __shared__ int lds_cnt[kMaxE];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
+    const int grp = lane / GS, sl = lane % GS;
     for (int i = threadIdx.x; i < kMaxE; i += 256) lds_cnt[i] = 0;
     __syncthreads();
 
-    float ps[kVPL];
+    float ps[VPL];
 #pragma unroll
-    for (int i = 0; i < kVPL; i++) ps[i] = 0.f;
+    for (int i = 0; i < VPL; i++) ps[i] = 0.f;
 
-    const int t0 = blockIdx.x * kRouterTokensPerBlock + wave * kTokPerWave;
-    for (int tt = 0; tt < kTokPerWave; tt++) {
+    const int t0 = blockIdx.x * kRouterTokensPerBlock + wave * kTokPerWave + grp;
+    float z[VPL], zn[VPL];
+    auto fetch = [&](int t, float* dst) {
+        const float* zr = logits + (size_t)min(t, T - 1) * E;
+#pragma unroll
+        for (int i = 0; i < VPL; i++) {
+            const int e = sl + GS * i;
+            dst[i] = (e < E) ? zr[e] : 0.f;
+        }
+    };
+    fetch(t0, zn);
+    for (int tt = 0; tt < kTokPerWave; tt += TPW) {
         const int t = t0 + tt;
-        if (t >= T) break;
-        const float* zr = logits + (size_t)t * E;
-        float z[kVPL];
+#pragma unroll
+        for (int i = 0; i < VPL; i++) z[i] = zn[i];
+        if (tt + TPW < kTokPerWave) fetch(t + TPW, zn);          // the next token's logits, a round ahead
+        const bool live = t < T;                                  // uniform inside the group
         float ss = 0.f;
 #pragma unroll
-        for (int i = 0; i < kVPL; i++) {
-            const int e = lane + 64 * i;
-            z[i] = (e < E) ? zr[e] : 0.f;
-            ss += z[i] * z[i];
-        }
-        ss = wave_sum(ss);
-        const float scale = sigma_c / (sqrtf(ss) + eps);
+        for (int i = 0; i < VPL; i++) ss += z[i] * z[i];
 #pragma unroll
-        for (int i = 0; i < kVPL; i++) ps[i] += fmaxf(z[i], 0.f) * scale;
-
+        for (int o = GS / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        const float scale = sigma_c / (sqrtf(ss) + eps);
+        if (live) {
+#pragma unroll
+            for (int i = 0; i < VPL; i++) ps[i] += fmaxf(z[i], 0.f) * scale;
+        }
         unsigned taken = 0;
         for (int j = 0; j < k; j++) {
             float bv = -INFINITY;
             int bi = 0x7fffffff;
 #pragma unroll
-            for (int i = 0; i < kVPL; i++) {
-                const int e = lane + 64 * i;
+            for (int i = 0; i < VPL; i++) {
+                const int e = sl + GS * i;
                 const bool ok = (e < E) && !((taken >> i) & 1u);
                 if (ok && (z[i] > bv || bi == 0x7fffffff)) { bv = z[i]; bi = e; }
             }
 #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
+            for (int o = GS / 2; o > 0; o >>= 1) {
                 const float ov = __shfl_xor(bv, o, 64);
                 const int oi = __shfl_xor(bi, o, 64);
                 const bool other_valid = oi != 0x7fffffff;
@@ -65,16 +80,23 @@ __global__ __launch_bounds__(256) void route_score_topk_kernel(
                 const bool take = other_valid && (!mine_valid || ov > bv || (ov == bv && oi < bi));
                 if (take) { bv = ov; bi = oi; }
             }
-            if ((bi & 63) == lane) {
-                taken |= 1u << (bi >> 6);
-                atomicAdd(&lds_cnt[bi], 1);
-                topk_idx[(size_t)t * k + j] = bi;
-                topk_gate[(size_t)t * k + j] = fmaxf(bv, 0.f) * scale;
+            if (bi % GS == sl) {
+                taken |= 1u << (bi / GS);
+                if (live) {
+                    atomicAdd(&lds_cnt[bi], 1);
+                    topk_idx[(size_t)t * k + j] = bi;
+                    topk_gate[(size_t)t * k + j] = fmaxf(bv, 0.f) * scale;
+                }
             }
         }
     }
+    // score sums: over the token groups of the wavefront (fixed order), then over the wavefronts
 #pragma unroll
-    for (int i = 0; i < kVPL; i++) lds_ps[wave][lane + 64 * i] = ps[i];
+    for (int i = 0; i < VPL; i++) {
+#pragma unroll
+        for (int o = GS; o < 64; o <<= 1) ps[i] += __shfl_xor(ps[i], o, 64);
+        if (grp == 0 && sl + GS * i < kMaxE) lds_ps[wave][sl + GS * i] = ps[i];
+    }
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += 256) {
         float v = lds_ps[0][e];
@@ -202,8 +224,16 @@ hipError_t launch_route_score_topk(const unipool_shape& s, const float* logits, 
                                    float* topk_gate, int32_t* counts, float* psum,
                                    int32_t* cnt_part, float* psum_part, hipStream_t st) {
     const int nblocks = cdiv(s.T, kRouterTokensPerBlock);
-    route_score_topk_kernel<<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps,
-                                                     topk_idx, topk_gate, cnt_part, psum_part);
+    // lanes per token and logits per lane by pool size
+    if (s.E <= 128)
+        route_score_topk_kernel<16, 8><<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps,
+                                                                topk_idx, topk_gate, cnt_part, psum_part);
+    else if (s.E <= 256)
+        route_score_topk_kernel<16, 16><<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps,
+                                                                 topk_idx, topk_gate, cnt_part, psum_part);
+    else
+        route_score_topk_kernel<32, 16><<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps,
+                                                                 topk_idx, topk_gate, cnt_part, psum_part);
     route_finalize_kernel<<<s.E, 256, 0, st>>>(cnt_part, psum_part, nblocks, s.E, counts, psum);
     return hipGetLastError();
 }
