@@ -24,7 +24,11 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per gemm_xw launch from rocprofv3 counters (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
 # of the 1 GiB copy below), averaged over the four expert-FFN launches of a layer; see
 # profiles/gemm_counters_C5.txt.  Not measured for the other workloads.
-MEASURED_XW_TRAFFIC_BYTES = {"C5": 7.8e9}
+MEASURED_XW_TRAFFIC_BYTES = {"C5": 7.5e9}
+# The same average from the L2's own request counters (TCC_EA0_RDREQ_sum x 128 B, every request of these
+# kernels is a 128-byte one, + WRITE_SIZE): FETCH_SIZE prices a request that is neither 32 bytes nor a
+# "bubble" at 64 bytes, which fits the copy kernel after scaling by 2 but overstates these kernels.
+MEASURED_XW_TRAFFIC_BYTES_RDREQ = {"C5": 6.0e9}
 
 
 def parse():
@@ -152,6 +156,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": xw_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": xw_tflops / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_XW_TRAFFIC_BYTES.get(a.workload),
+                     "traffic_from_l2_read_requests": MEASURED_XW_TRAFFIC_BYTES_RDREQ.get(a.workload),
                      "algorithmic_bytes_per_launch": (12.0 * w.E * w.d * w.f + 8.0 * S * w.d + 20.0 * S * w.f) / 4.0,
                      "kernel": "gemm_xw (grouped bf16 GEMM: gate-up, down, dH, dX)",
                      "avg_launch_ms": avg_xw_ms, "launches": n_xw,
