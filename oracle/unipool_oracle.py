@@ -24,7 +24,9 @@ Pins (tests/test_oracle_*.py): dense brute force of Eq. 2 with Python loops,
 full-sort top-k, permutation invariants, NormRouter closed forms, pool-loss
 closed forms (uniform usage, single expert, L = 1 reducing to Eq. 3, Eq. 6
 identity), central finite differences for every gradient, E = 1 reducing to a
-dense SwiGLU MLP.  `estimate_c` (App. G, Alg. 1) is pinned only statistically.
+dense SwiGLU MLP; the one-step-behind loop against a hand count of the previous
+micro-batch's slots and finite differences of the lagged objective; the
+recompute half against the forward record.  `estimate_c` (App. G, Alg. 1) is pinned only statistically.
 """
 from __future__ import annotations
 
@@ -144,6 +146,23 @@ def expert_ffn_fwd(x_perm, offsets, w_gate, w_up, w_down):
             a[r0:r1], b[r0:r1], h[r0:r1], y[r0:r1] = expert_apply(
                 x_perm[r0:r1], w_gate[e], w_up[e], w_down[e])
     return a, b, h, y
+
+
+def expert_ffn_recompute(x_perm, offsets, w_gate, w_up):
+    """App. C (activation checkpointing with MoE recompute): A, B and H of every group
+    again from the kept rows -- the gate and up projections and the SwiGLU product of
+    expert_ffn_fwd, without the down projection."""
+    x_perm = np.asarray(x_perm, F64)
+    S = x_perm.shape[0]
+    E, f, _ = w_gate.shape
+    a = np.zeros((S, f), F64)
+    b = np.zeros((S, f), F64)
+    for e in range(E):
+        r0, r1 = int(offsets[e]), int(offsets[e + 1])
+        if r1 > r0:
+            a[r0:r1] = x_perm[r0:r1] @ np.asarray(w_gate[e], F64).T
+            b[r0:r1] = x_perm[r0:r1] @ np.asarray(w_up[e], F64).T
+    return a, b, silu(a) * b
 
 
 def combine(y_perm, row_of_slot, gate=None):
@@ -328,6 +347,22 @@ def pool_step(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps,
         bws.append(bw)
     return dict(fw=fws, bw=bws, counts=counts, psum=psum, pool_counts=pool_counts, fbar=fbar,
                 loss=loss, coef=coef, dw_gate=dwg, dw_up=dwu, dw_down=dwd)
+
+
+def micro_batch_loop(batches, w_routers, w_gate, w_up, w_down, k, sigmas, c, eps, alpha, fbar0=None):
+    """App. F, one-step-behind: micro-batch m takes the usage statistic fbar of micro-batch
+    m-1 as a constant; the first one takes `fbar0`, or, when that is None, its own (the
+    paper does not say what the first micro-batch uses).  `batches` is a list of
+    (xs, grad_outs).  Returns the list of pool_step results; entry m's "fbar" is the
+    statistic that micro-batch m+1 uses."""
+    results = []
+    fbar = fbar0
+    for xs, grad_outs in batches:
+        r = pool_step(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps, alpha,
+                      fbar_in=fbar)
+        results.append(r)
+        fbar = r["fbar"]
+    return results
 
 
 def objective(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps, alpha, fbar):

@@ -1,0 +1,118 @@
+"""Pins for the oracle's one-step-behind micro-batch loop (App. F) and for the recompute half of
+the expert FFN (App. C).  None of them calls the function under test to make its own expectation:
+the lagged statistic is counted by hand with Python loops, the gradients come from central finite
+differences of the float64 objective, the recompute is compared with a dense per-row evaluation."""
+import numpy as np
+import pytest
+
+from oracle import unipool_oracle as O
+from tests.test_oracle_backward import HP, _fd, _margin_ok, problem
+
+
+def _batches(n, seed0):
+    """n micro-batches that share router and pool weights; returns (batches, weights...)."""
+    seed = seed0
+    out = []
+    base = None
+    while len(out) < n:
+        xs, wrs, wg, wu, wd, gs, sigmas = problem(seed=seed)
+        seed += 1
+        if base is None:
+            base = (wrs, wg, wu, wd, sigmas)
+        if _margin_ok(xs, base[0], HP["k"]):
+            out.append((xs, gs))
+    return out, base
+
+
+def _hand_fbar(xs, wrs, k, E):
+    """fbar of one micro-batch, counted slot by slot (Eq. 4): no vector code, no oracle call."""
+    L = len(xs)
+    fbar = [0.0] * E
+    for l in range(L):
+        z = xs[l] @ wrs[l].T
+        T = z.shape[0]
+        for t in range(T):
+            order = sorted(range(E), key=lambda i: (-z[t, i], i))
+            for i in order[:k]:
+                fbar[i] += 1.0 / (T * k * L)
+    return np.array(fbar)
+
+
+def test_second_micro_batch_uses_the_first_one_s_statistic():
+    batches, (wrs, wg, wu, wd, sigmas) = _batches(3, 40)
+    res = O.micro_batch_loop(batches, wrs, wg, wu, wd, HP["k"], sigmas, HP["c"], HP["eps"], HP["alpha"])
+    E = wg.shape[0]
+    L = len(wrs)
+    T = batches[0][0][0].shape[0]
+    for m in (1, 2):
+        prev = _hand_fbar(batches[m - 1][0], wrs, HP["k"], E)
+        cur = _hand_fbar(batches[m][0], wrs, HP["k"], E)
+        assert np.abs(prev - cur).max() > 1e-3          # the two statistics differ: the test can tell them apart
+        # loss of micro-batch m = alpha * M * sum_i fbar_i(m-1) * Pbar_i(m)        (Eq. 5 with the lagged fbar)
+        pbar = np.zeros(E)
+        for l in range(L):
+            z = batches[m][0][l] @ wrs[l].T
+            s = sigmas[l] * HP["c"] * np.maximum(z / (np.linalg.norm(z, axis=1, keepdims=True) + HP["eps"]), 0.0)
+            pbar += s.mean(axis=0) / L
+        assert res[m]["loss"] == pytest.approx(HP["alpha"] * E * float(prev @ pbar), rel=1e-12)
+        assert np.allclose(res[m]["coef"], HP["alpha"] * E * prev / (L * T), rtol=1e-12, atol=0)
+        assert np.allclose(res[m]["fbar"], cur, rtol=1e-12, atol=1e-15)     # what is handed on is the own statistic
+    # the first micro-batch uses its own statistic
+    own = _hand_fbar(batches[0][0], wrs, HP["k"], E)
+    assert np.allclose(res[0]["coef"], HP["alpha"] * E * own / (L * T), rtol=1e-12, atol=0)
+
+
+def test_lagged_gradients_by_central_differences():
+    batches, (wrs, wg, wu, wd, sigmas) = _batches(2, 60)
+    res = O.micro_batch_loop(batches, wrs, wg, wu, wd, HP["k"], sigmas, HP["c"], HP["eps"], HP["alpha"])
+    xs, gs = batches[1]
+    fbar_prev = _hand_fbar(batches[0][0], wrs, HP["k"], wg.shape[0])
+
+    def lam():
+        return O.objective(xs, wrs, wg, wu, wd, gs, HP["k"], sigmas, HP["c"], HP["eps"], HP["alpha"], fbar_prev)
+
+    rng = np.random.default_rng(3)
+    for l in range(len(xs)):
+        for arr, grad in ((wrs[l], res[1]["bw"][l]["dw_router"]), (xs[l], res[1]["bw"][l]["dx"])):
+            scale = np.max(np.abs(grad)) + 1e-30
+            for _ in range(10):
+                index = tuple(int(rng.integers(0, n)) for n in arr.shape)
+                num = _fd(lam, arr, index)
+                assert abs(num - grad[index]) <= 2e-7 * scale + 1e-9, (l, index, num, grad[index])
+
+
+def test_lagged_equals_same_step_when_the_batches_repeat():
+    batches, (wrs, wg, wu, wd, sigmas) = _batches(1, 80)
+    twice = [batches[0], batches[0]]
+    res = O.micro_batch_loop(twice, wrs, wg, wu, wd, HP["k"], sigmas, HP["c"], HP["eps"], HP["alpha"])
+    assert res[1]["loss"] == pytest.approx(res[0]["loss"], rel=1e-14)
+    for l in range(len(wrs)):
+        assert np.array_equal(res[1]["bw"][l]["dw_router"], res[0]["bw"][l]["dw_router"])
+
+
+def test_given_initial_statistic_is_used_as_is():
+    batches, (wrs, wg, wu, wd, sigmas) = _batches(1, 90)
+    E = wg.shape[0]
+    f0 = np.full(E, 1.0 / E)
+    res = O.micro_batch_loop(batches, wrs, wg, wu, wd, HP["k"], sigmas, HP["c"], HP["eps"], HP["alpha"], fbar0=f0)
+    L, T = len(wrs), batches[0][0][0].shape[0]
+    # uniform fbar: every expert's coefficient is alpha / (L T)
+    assert np.allclose(res[0]["coef"], HP["alpha"] / (L * T), rtol=1e-12, atol=0)
+
+
+def test_recompute_matches_dense_rows():
+    rng = np.random.default_rng(5)
+    E, f, d, S = 4, 5, 6, 17
+    wg = rng.standard_normal((E, f, d))
+    wu = rng.standard_normal((E, f, d))
+    x = rng.standard_normal((S, d))
+    offsets = np.array([0, 6, 6, 13, 17])            # expert 1 has no rows
+    a, b, h = O.expert_ffn_recompute(x, offsets, wg, wu)
+    for row in range(S):
+        e = int(np.searchsorted(offsets, row, side="right") - 1)
+        for n in range(f):
+            aa = sum(x[row, c] * wg[e, n, c] for c in range(d))
+            bb = sum(x[row, c] * wu[e, n, c] for c in range(d))
+            assert a[row, n] == pytest.approx(aa, rel=1e-12, abs=1e-14)
+            assert b[row, n] == pytest.approx(bb, rel=1e-12, abs=1e-14)
+            assert h[row, n] == pytest.approx(aa / (1.0 + np.exp(-aa)) * bb, rel=1e-12, abs=1e-14)
