@@ -139,6 +139,19 @@ int unipool_expert_ffn_fwd(const unipool_shape* shape, const void* x_perm,
                            void* y_perm, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * First half of unipool_expert_ffn_fwd alone, for training with activation recomputation
+ * (App. C, hyperparameter details: activation checkpointing with MoE layer recompute): a caller that
+ * did not keep A and B of a layer runs this before unipool_expert_ffn_bwd.  Same arithmetic as
+ * in the forward pass, so the three tensors come out bit-identical to the forward's.
+ * in : x_perm [S, d] act;  expert_offsets [E+1];  w_gate_up (see top).
+ * out: act_a, act_b, act_h [S, f] act.
+ */
+int unipool_expert_ffn_recompute(const unipool_shape* shape, const void* x_perm,
+                                 const int32_t* expert_offsets, const void* w_gate_up,
+                                 void* act_a, void* act_b, void* act_h,
+                                 void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Backward of the pool experts for one layer.
  *   dH = dY W_down;  dA = dH * B * silu'(A);  dB = dH * silu(A);
  *   dX_perm = dA W_gate + dB W_up;

@@ -28,7 +28,7 @@ class Shape(ctypes.Structure):
 
 ENTRY_POINTS = ("unipool_workspace_bytes", "unipool_last_error", "unipool_version", "unipool_route",
                 "unipool_route_bwd", "unipool_permute", "unipool_expert_ffn_fwd",
-                "unipool_expert_ffn_bwd", "unipool_expert_wgrad", "unipool_combine",
+                "unipool_expert_ffn_recompute", "unipool_expert_ffn_bwd", "unipool_expert_wgrad", "unipool_combine",
                 "unipool_combine_bwd", "unipool_pool_aux_loss")
 
 
@@ -58,6 +58,7 @@ def load_library():
             "unipool_route_bwd": [SP] + [P] * 9 + [I, P, Z, P],
             "unipool_permute": [SP] + [P] * 7 + [P, Z, P],
             "unipool_expert_ffn_fwd": [SP] + [P] * 8 + [P, Z, P],
+            "unipool_expert_ffn_recompute": [SP] + [P] * 6 + [P, Z, P],
             "unipool_expert_ffn_bwd": [SP] + [P] * 12 + [P, Z, P],
             "unipool_expert_wgrad": [SP, I] + [P] * 7 + [I, P, Z, P],
             "unipool_combine": [SP] + [P] * 4 + [P, Z, P],
@@ -149,6 +150,14 @@ def expert_ffn_fwd(shape, x_perm, expert_offsets, w_gate_up, w_down, act_a, act_
                                                  _ptr(w_gate_up), _ptr(w_down), _ptr(act_a),
                                                  _ptr(act_b), _ptr(act_h), _ptr(y_perm), p, n,
                                                  _stream(stream)), "unipool_expert_ffn_fwd")
+
+
+def expert_ffn_recompute(shape, x_perm, expert_offsets, w_gate_up, act_a, act_b, act_h, ws, stream=None):
+    p, n = _ws(ws)
+    _check(load_library().unipool_expert_ffn_recompute(ctypes.byref(shape), _ptr(x_perm),
+                                                       _ptr(expert_offsets), _ptr(w_gate_up), _ptr(act_a),
+                                                       _ptr(act_b), _ptr(act_h), p, n, _stream(stream)),
+           "unipool_expert_ffn_recompute")
 
 
 def expert_ffn_bwd(shape, dy_perm, x_perm, act_a, act_b, act_h, expert_offsets, w_gate_up, w_down,

@@ -230,6 +230,25 @@ int unipool_expert_ffn_fwd(const unipool_shape* shape, const void* x_perm,
     return check_hip(e, "unipool_expert_ffn_fwd");
 }
 
+int unipool_expert_ffn_recompute(const unipool_shape* shape, const void* x_perm,
+                                 const int32_t* expert_offsets, const void* w_gate_up,
+                                 void* act_a, void* act_b, void* act_h, void* ws, size_t ws_bytes,
+                                 void* stream) {
+    PROLOGUE();
+    REQUIRE_PTR(x_perm); REQUIRE_PTR(expert_offsets); REQUIRE_PTR(w_gate_up);
+    REQUIRE_PTR(act_a); REQUIRE_PTR(act_b); REQUIRE_PTR(act_h);
+    NEED_WS();
+    const WsLayout w = ws_layout(*shape);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (mfma_ffn_supported(*shape) && !force_naive())
+        e = mfma_ffn_gate_up(*shape, x_perm, expert_offsets, w_gate_up, act_a, act_b, act_h,
+                             (int32_t*)((char*)ws + w.tile_meta), st);
+    else
+        e = naive_ffn_gate_up(*shape, x_perm, expert_offsets, w_gate_up, act_a, act_b, act_h, st);
+    return check_hip(e, "unipool_expert_ffn_recompute");
+}
+
 int unipool_expert_ffn_bwd(const unipool_shape* shape, const void* dy_perm, const void* x_perm,
                            const void* act_a, const void* act_b, const void* act_h,
                            const int32_t* expert_offsets, const void* w_gate_up, const void* w_down,

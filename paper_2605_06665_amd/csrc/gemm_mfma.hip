@@ -1147,9 +1147,9 @@ hipError_t mfma_logits(const unipool_shape& s, const void* x, const void* w, flo
     return run_xw<true, EPI_F32>(a, cdiv(s.T, kBM), st);
 }
 
-hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
-                        const void* wgu, const void* wd, void* a_out, void* b_out, void* h_out,
-                        void* y, int32_t* tile_meta, hipStream_t st) {
+hipError_t mfma_ffn_gate_up(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
+                           const void* wgu, void* a_out, void* b_out, void* h_out, int32_t* tile_meta,
+                           hipStream_t st) {
     const int S = s.T * s.k, d = s.d_model, f = s.d_ff;
     const int max_tiles = S / kBM + s.E;
     hipError_t e = build_tiles(offsets, s.E, S, tile_meta, st);
@@ -1160,7 +1160,15 @@ hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_
     a.K = d; a.N = f; a.n_tiles_n = cdiv(f, kBN / 2);
     a.tile_meta = tile_meta; a.out0 = a_out; a.out1 = b_out; a.out2 = h_out; a.ldo = f;
     a.up_rows = f;
-    e = run_xw<true, EPI_SWIGLU_FWD>(a, max_tiles, st);
+    return run_xw<true, EPI_SWIGLU_FWD>(a, max_tiles, st);
+}
+
+hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
+                        const void* wgu, const void* wd, void* a_out, void* b_out, void* h_out,
+                        void* y, int32_t* tile_meta, hipStream_t st) {
+    const int S = s.T * s.k, d = s.d_model, f = s.d_ff;
+    const int max_tiles = S / kBM + s.E;
+    hipError_t e = mfma_ffn_gate_up(s, x_perm, offsets, wgu, a_out, b_out, h_out, tile_meta, st);
     if (e != hipSuccess) return e;
     GemmArgs b = {};
     b.X = (const bf16*)h_out; b.ldx = f;

@@ -168,6 +168,14 @@ hipError_t naive_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32
     return hipGetLastError();
 }
 
+hipError_t naive_ffn_gate_up(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
+                            const void* wgu, void* a, void* b, void* h, hipStream_t st) {
+    const int S = s.T * s.k;
+    DISPATCH((gate_up_kernel<TA><<<blocks_for((size_t)S * s.d_ff), 256, 0, st>>>(
+        (const TA*)x_perm, offsets, (const TA*)wgu, S, s.d_model, s.d_ff, s.E, (TA*)a, (TA*)b, (TA*)h)));
+    return hipGetLastError();
+}
+
 hipError_t naive_ffn_dgrad(const unipool_shape& s, const void* dy, const void* a, const void* b,
                            const int32_t* offsets, const void* wgu, const void* wd, void* dx,
                            void* d_act, hipStream_t st) {

@@ -38,6 +38,8 @@ hipError_t naive_logits(const unipool_shape& s, const void* x, const void* w, fl
 hipError_t naive_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
                          const void* wgu, const void* wd, void* a, void* b, void* h, void* y,
                          hipStream_t st);
+hipError_t naive_ffn_gate_up(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
+                            const void* wgu, void* a, void* b, void* h, hipStream_t st);
 hipError_t naive_ffn_dgrad(const unipool_shape& s, const void* dy, const void* a, const void* b,
                            const int32_t* offsets, const void* wgu, const void* wd, void* dx,
                            void* d_act, hipStream_t st);
@@ -56,6 +58,9 @@ hipError_t mfma_logits(const unipool_shape& s, const void* x, const void* w, flo
 hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
                         const void* wgu, const void* wd, void* a, void* b, void* h, void* y,
                         int32_t* tile_meta, hipStream_t st);
+hipError_t mfma_ffn_gate_up(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
+                           const void* wgu, void* a, void* b, void* h, int32_t* tile_meta,
+                           hipStream_t st);
 hipError_t mfma_ffn_dgrad(const unipool_shape& s, const void* dy, const void* a, const void* b,
                           const int32_t* offsets, const void* wgu, const void* wd, void* dx,
                           void* d_act, int32_t* tile_meta, hipStream_t st);

@@ -40,9 +40,22 @@ class LayerState:
 
 
 class PoolStep:
+    """Sequences the entry points over the L layers that share the pool.
+
+    wgrad     "pool": one weight-gradient pass over all layers at the end of the backward pass;
+              "layer": accumulate into the float gradients layer by layer.
+    recompute keep one shared pair of A / B buffers instead of one per layer and rebuild a layer's
+              A and B (unipool_expert_ffn_recompute) right before its backward pass (App. C:
+              activation checkpointing with MoE recompute).  Results are bit-identical.
+    lagged    App. F, one-step-behind: micro-batch m uses the usage statistic fbar of micro-batch
+              m-1, held constant; the first micro-batch uses its own.  The statistic lives in two
+              device buffers used in turn and is part of state_dict()."""
+
     def __init__(self, T, d_model, d_ff, E, k, L, dtype, c, eps, alpha_pool, device="cuda:0",
-                 wgrad="pool"):
+                 wgrad="pool", recompute=False, lagged=False):
         assert wgrad in ("pool", "layer")
+        self.recompute, self.lagged = bool(recompute), bool(lagged)
+        self.micro_batches_done = 0
         self.T, self.d, self.f, self.E, self.k, self.L = T, d_model, d_ff, E, k, L
         self.dtype = dtype
         self.c, self.eps, self.alpha = c, eps, alpha_pool
@@ -60,17 +73,21 @@ class PoolStep:
         self.counts = torch.zeros((L, E), **i32)
         self.psum = torch.zeros((L, E), **f32)
         self.pool_counts = torch.zeros(E, **i32)
-        self.fbar = torch.zeros(E, **f32)
+        self._fbar2 = [torch.zeros(E, **f32), torch.zeros(E, **f32)]
+        self.fbar = self._fbar2[0]           # fbar of the micro-batch that ran last
         self.loss = torch.zeros(1, **f32)
         self.aux_coef = torch.zeros(E, **f32)
         self.layers: List[LayerState] = []
+        shared_ab = (torch.empty((S, f), **act), torch.empty((S, f), **act)) if self.recompute else None
         for _ in range(L):
             st = LayerState(
                 topk_idx=torch.empty((T, k), **i32), topk_gate=torch.empty((T, k), **f32),
                 logits=torch.empty((T, E), **f32), x_perm=torch.empty((S, d), **act),
                 offsets=torch.empty(E + 1, **i32), row_of_slot=torch.empty((T, k), **i32),
-                slot_of_row=torch.empty(S, **i32), act_a=torch.empty((S, f), **act),
-                act_b=torch.empty((S, f), **act), act_h=torch.empty((S, f), **act),
+                slot_of_row=torch.empty(S, **i32),
+                act_a=shared_ab[0] if self.recompute else torch.empty((S, f), **act),
+                act_b=shared_ab[1] if self.recompute else torch.empty((S, f), **act),
+                act_h=torch.empty((S, f), **act),
                 y_perm=torch.empty((S, d), **act), out=torch.empty((T, d), **act))
             st.dgate = torch.empty((T, k), **f32)
             st.dx = torch.empty((T, d), **act)
@@ -118,9 +135,28 @@ class PoolStep:
         return st.out
 
     def aux_loss(self, fbar_in=None):
-        self._call(B.pool_aux_loss, self.shape(1.0), self.counts, self.psum, fbar_in, self.pool_counts, self.fbar,
+        """Pool loss of the layers run so far.  In lagged mode the statistic of the previous
+        micro-batch is used (none given, none run yet: the current one) and the new one is kept."""
+        out = self.fbar
+        if self.lagged:
+            if fbar_in is None and self.micro_batches_done > 0:
+                fbar_in = self._fbar2[(self.micro_batches_done - 1) % 2]
+            out = self._fbar2[self.micro_batches_done % 2]
+        self._call(B.pool_aux_loss, self.shape(1.0), self.counts, self.psum, fbar_in, self.pool_counts, out,
                         self.loss, self.aux_coef, self.ws)
+        self.fbar = out
+        self.micro_batches_done += 1
         return self.loss
+
+    def state_dict(self):
+        """What a checkpoint of the micro-batch loop has to hold."""
+        return {"micro_batches_done": self.micro_batches_done, "fbar": self.fbar.detach().cpu().clone()}
+
+    def load_state_dict(self, state):
+        self.micro_batches_done = int(state["micro_batches_done"])
+        if self.micro_batches_done > 0:
+            self._fbar2[(self.micro_batches_done - 1) % 2].copy_(state["fbar"].to(self.dev))
+            self.fbar = self._fbar2[(self.micro_batches_done - 1) % 2]
 
     # ------------------------------------------------------------------ backward
     def begin_backward(self):
@@ -133,6 +169,9 @@ class PoolStep:
         slot = l if self.wgrad == "pool" else 0
         dy, dact = self._dy[slot], self._dact[slot]
         self._call(B.combine_bwd, sh, grad_out, st.y_perm, st.row_of_slot, st.topk_gate, dy, st.dgate, ws)
+        if self.recompute:
+            self._call(B.expert_ffn_recompute, sh, st.x_perm, st.offsets, w_gate_up, st.act_a, st.act_b,
+                       st.act_h, ws)
         dwgu = None if self.wgrad == "pool" else self.d_w_gate_up
         dwd = None if self.wgrad == "pool" else self.d_w_down
         self._call(B.expert_ffn_bwd, sh, dy, st.x_perm, st.act_a, st.act_b, st.act_h, st.offsets, w_gate_up, w_down,
