@@ -7,6 +7,7 @@ router-bwd) with the pool weight gradient.  Inputs are synthetic, drawn on the d
 timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--wgrad pool|layer]
+                  [--recompute] [--lagged]
 """
 import argparse
 import json
@@ -38,6 +39,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--wgrad", default="pool", choices=["pool", "layer"])
+    ap.add_argument("--recompute", action="store_true",
+                    help="keep one shared pair of A/B buffers and rebuild them before each layer's backward")
+    ap.add_argument("--lagged", action="store_true", help="one-step-behind usage statistic across steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-tokens", type=int, default=1024)
     return ap.parse_args()
@@ -89,7 +93,8 @@ def main():
     wg, wu, wd = W.gen_pool_weights_torch(w, dev)
     wgu = torch.cat([wg, wu], dim=1).contiguous()
     sigmas = [w.sigma] * w.L
-    ps = PoolStep(w.T, w.d, w.f, w.E, w.k, w.L, dtype, w.c, w.eps, w.alpha, device=dev, wgrad=a.wgrad)
+    ps = PoolStep(w.T, w.d, w.f, w.E, w.k, w.L, dtype, w.c, w.eps, w.alpha, device=dev, wgrad=a.wgrad,
+                  recompute=a.recompute, lagged=a.lagged)
     # one plain device-to-device copy of known size (1 GiB read + 1 GiB write): the reference
     # against which the HBM byte counters of a profiler run are scaled
     cal_src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
@@ -116,14 +121,17 @@ def main():
         agg.setdefault(name, []).append(e0.elapsed_time(e1))
     S = w.S
     gemm_flops_third = 6.0 * S * w.d * w.f            # one of fwd / dgrad / wgrad, per layer
-    n_xw = 4 * w.L * a.steps                          # gate-up, down, dH, dX launches
-    t_xw_ms = sum(agg.get("expert_ffn_fwd", [])) + sum(agg.get("expert_ffn_bwd", []))
-    xw_flops_per_launch = 2.0 * gemm_flops_third / 4.0
+    n_per_layer = 5 if a.recompute else 4             # gate-up, down, dH, dX (and gate-up again) launches
+    n_xw = n_per_layer * w.L * a.steps
+    t_xw_ms = (sum(agg.get("expert_ffn_fwd", [])) + sum(agg.get("expert_ffn_bwd", []))
+               + sum(agg.get("expert_ffn_recompute", [])))
+    xw_flops_per_launch = (2.0 * gemm_flops_third + (4.0 * S * w.d * w.f if a.recompute else 0.0)) / n_per_layer
     avg_xw_ms = t_xw_ms / n_xw
     xw_tflops = xw_flops_per_launch / (avg_xw_ms * 1e-3) / 1e12
     t_wg_ms = sum(agg.get("expert_wgrad", []))
-    all_gemm_tflops = 3.0 * gemm_flops_third * w.L * a.steps / ((t_xw_ms + t_wg_ms) * 1e-3) / 1e12 \
-        if a.wgrad == "pool" else 3.0 * gemm_flops_third * w.L * a.steps / (t_xw_ms * 1e-3) / 1e12
+    gemm_flops_layer = 3.0 * gemm_flops_third + (4.0 * S * w.d * w.f if a.recompute else 0.0)
+    all_gemm_tflops = gemm_flops_layer * w.L * a.steps / ((t_xw_ms + t_wg_ms) * 1e-3) / 1e12 \
+        if a.wgrad == "pool" else gemm_flops_layer * w.L * a.steps / (t_xw_ms * 1e-3) / 1e12
     act_b = 2 if w.dtype == "bf16" else 4
 
     def hbm(name, nbytes, calls_per_step):
@@ -151,7 +159,8 @@ def main():
         "warmup": a.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "L": w.L, "E": w.E, "d_model": w.d, "d_ff": w.f, "top_k": w.k,
-                   "tokens_per_layer": w.T, "skew": w.skew, "wgrad": a.wgrad,
+                   "tokens_per_layer": w.T, "skew": w.skew, "wgrad": a.wgrad, "recompute": a.recompute,
+                   "lagged_statistic": a.lagged,
                    "tokens_counted": "L*T token-layer evaluations per step"},
         "roofline": {"bound": "mfma", "achieved": xw_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": xw_tflops / PEAK_BF16_TFLOPS,
