@@ -323,9 +323,15 @@ def moe_layer_bwd(fw, x, w_router, w_gate, w_up, w_down, dout, aux_coef, k, sigm
 # Whole step over the L layers that share the pool
 # ---------------------------------------------------------------------------
 def pool_step(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps, alpha,
-              fbar_in=None, idxs=None):
-    """Forward of all layers, pool loss (Eq. 5), backward of all layers.
-    Expert weight gradients are summed over the layers (one shared pool)."""
+              fbar_in=None, idxs=None, aux="pool"):
+    """Forward of all layers, auxiliary loss, backward of all layers.
+    Expert weight gradients are summed over the layers (one shared pool).
+
+    aux = "pool":  the pool-level loss of Eq. 5 over all the layers;
+    aux = "layer": the per-layer loss of Eq. 3 for every layer on its own, each entering the
+                   objective with weight one (the ablation row "shared pool + layer aux",
+                   Sec. 5.4); "loss" is then their sum, "loss_layers" the list, and "coef"
+                   holds one coefficient vector per layer."""
     L = len(xs)
     T = xs[0].shape[0]
     fws = [moe_layer_fwd(xs[l], w_routers[l], w_gate, w_up, w_down, k, sigmas[l], c, eps,
@@ -333,20 +339,44 @@ def pool_step(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps,
            for l in range(L)]
     counts = np.stack([fw["counts"] for fw in fws])
     psum = np.stack([fw["psum"] for fw in fws])
-    pool_counts, fbar, loss, coef = pool_aux_loss(counts, psum, T, k, alpha, fbar_in)
+    loss_layers = None
+    if aux == "pool":
+        pool_counts, fbar, loss, coef = pool_aux_loss(counts, psum, T, k, alpha, fbar_in)
+        coefs = [coef] * L
+    else:
+        assert aux == "layer" and fbar_in is None
+        per = [pool_aux_loss(counts[l:l + 1], psum[l:l + 1], T, k, alpha) for l in range(L)]
+        pool_counts = counts.sum(axis=0).astype(np.int64)
+        fbar = np.stack([p[1] for p in per])                 # f^(l), one row per layer
+        loss_layers = [p[2] for p in per]
+        loss = float(sum(loss_layers))
+        coefs = [p[3] for p in per]
+        coef = np.stack(coefs)
     dwg = np.zeros(w_gate.shape, F64)
     dwu = np.zeros(w_up.shape, F64)
     dwd = np.zeros(w_down.shape, F64)
     bws = []
     for l in range(L):
-        bw = moe_layer_bwd(fws[l], xs[l], w_routers[l], w_gate, w_up, w_down, grad_outs[l], coef,
+        bw = moe_layer_bwd(fws[l], xs[l], w_routers[l], w_gate, w_up, w_down, grad_outs[l], coefs[l],
                            k, sigmas[l], c, eps)
         dwg += bw["dw_gate"]
         dwu += bw["dw_up"]
         dwd += bw["dw_down"]
         bws.append(bw)
     return dict(fw=fws, bw=bws, counts=counts, psum=psum, pool_counts=pool_counts, fbar=fbar,
-                loss=loss, coef=coef, dw_gate=dwg, dw_up=dwu, dw_down=dwd)
+                loss=loss, loss_layers=loss_layers, coef=coef, dw_gate=dwg, dw_up=dwu, dw_down=dwd)
+
+
+def pool_groups_step(groups, k, c, eps, alpha):
+    """Sharing scope G (Sec. 5.4): the layers are cut into G groups over depth, every group
+    routes into a pool of its own and carries its own pool loss (Eq. 5 over the group's
+    layers); G = 1 is the fully shared pool, one layer per group is the layer-private MoE
+    with the loss of Eq. 3.  `groups` is a list of dicts with keys xs, w_routers, w_gate,
+    w_up, w_down, grad_outs, sigmas.  Returns the per-group pool_step results and the sum
+    of the group losses."""
+    results = [pool_step(g["xs"], g["w_routers"], g["w_gate"], g["w_up"], g["w_down"], g["grad_outs"],
+                         k, g["sigmas"], c, eps, alpha) for g in groups]
+    return results, float(sum(r["loss"] for r in results))
 
 
 def micro_batch_loop(batches, w_routers, w_gate, w_up, w_down, k, sigmas, c, eps, alpha, fbar0=None):

@@ -47,13 +47,19 @@ class PoolStep:
     recompute keep one shared pair of A / B buffers instead of one per layer and rebuild a layer's
               A and B (unipool_expert_ffn_recompute) right before its backward pass (App. C:
               activation checkpointing with MoE recompute).  Results are bit-identical.
+    aux       "pool": the pool-level loss (Eq. 5) over all L layers; "layer": the per-layer loss
+              (Eq. 3) for every layer on its own, each with weight one (the ablation row "shared pool
+              + layer aux"): unipool_pool_aux_loss is then called once per layer with L = 1, the losses
+              are in loss_layers[L] and every layer's backward pass gets its own coefficients.
     lagged    App. F, one-step-behind: micro-batch m uses the usage statistic fbar of micro-batch
               m-1, held constant; the first micro-batch uses its own.  The statistic lives in two
               device buffers used in turn and is part of state_dict()."""
 
     def __init__(self, T, d_model, d_ff, E, k, L, dtype, c, eps, alpha_pool, device="cuda:0",
-                 wgrad="pool", recompute=False, lagged=False):
-        assert wgrad in ("pool", "layer")
+                 wgrad="pool", recompute=False, lagged=False, aux="pool"):
+        assert wgrad in ("pool", "layer") and aux in ("pool", "layer")
+        assert not (lagged and aux == "layer"), "the lagged statistic belongs to the pool loss"
+        self.aux = aux
         self.recompute, self.lagged = bool(recompute), bool(lagged)
         self.micro_batches_done = 0
         self.T, self.d, self.f, self.E, self.k, self.L = T, d_model, d_ff, E, k, L
@@ -77,6 +83,11 @@ class PoolStep:
         self.fbar = self._fbar2[0]           # fbar of the micro-batch that ran last
         self.loss = torch.zeros(1, **f32)
         self.aux_coef = torch.zeros(E, **f32)
+        if aux == "layer":
+            self.loss_layers = torch.zeros(L, **f32)
+            self.aux_coef_layers = torch.zeros((L, E), **f32)
+            self.f_layers = torch.zeros((L, E), **f32)
+            self._pool_counts_layers = torch.zeros((L, E), **i32)
         self.layers: List[LayerState] = []
         shared_ab = (torch.empty((S, f), **act), torch.empty((S, f), **act)) if self.recompute else None
         for _ in range(L):
@@ -108,8 +119,8 @@ class PoolStep:
                           tab([s.act_h for s in self.layers]), tab(self._dy),
                           tab([s.offsets for s in self.layers]))
 
-    def shape(self, sigma: float) -> B.Shape:
-        return B.Shape(T=self.T, d_model=self.d, d_ff=self.f, E=self.E, k=self.k, L=self.L,
+    def shape(self, sigma: float, L=None) -> B.Shape:
+        return B.Shape(T=self.T, d_model=self.d, d_ff=self.f, E=self.E, k=self.k, L=self.L if L is None else L,
                        dtype=self.dtype, sigma=float(sigma), c=self.c, eps=self.eps,
                        alpha_pool=self.alpha)
 
@@ -137,6 +148,14 @@ class PoolStep:
     def aux_loss(self, fbar_in=None):
         """Pool loss of the layers run so far.  In lagged mode the statistic of the previous
         micro-batch is used (none given, none run yet: the current one) and the new one is kept."""
+        if self.aux == "layer":
+            sh1 = self.shape(1.0, L=1)
+            for l in range(self.L):
+                self._call(B.pool_aux_loss, sh1, self.counts[l:l + 1], self.psum[l:l + 1], None,
+                           self._pool_counts_layers[l], self.f_layers[l], self.loss_layers[l:l + 1],
+                           self.aux_coef_layers[l], self.ws)
+            self.micro_batches_done += 1
+            return self.loss_layers
         out = self.fbar
         if self.lagged:
             if fbar_in is None and self.micro_batches_done > 0:
@@ -177,7 +196,8 @@ class PoolStep:
         self._call(B.expert_ffn_bwd, sh, dy, st.x_perm, st.act_a, st.act_b, st.act_h, st.offsets, w_gate_up, w_down,
                          self._dxp, dact, dwgu, dwd, ws)
         self._call(B.combine, sh, self._dxp, st.row_of_slot, None, st.dx, ws)            # backward of the dispatch
-        self._call(B.route_bwd, sh, x, w_router, st.logits, st.topk_idx, st.dgate, self.aux_coef, st.d_w_router,
+        coef = self.aux_coef if self.aux == "pool" else self.aux_coef_layers[l]
+        self._call(B.route_bwd, sh, x, w_router, st.logits, st.topk_idx, st.dgate, coef, st.d_w_router,
                     st.d_sigma, st.dx, True, ws)
         return st.dx
 
@@ -195,3 +215,20 @@ class PoolStep:
         for l in reversed(range(self.L)):
             self.backward_layer(l, xs[l], w_routers[l], sigmas[l], w_gate_up, w_down, grad_outs[l])
         self.end_backward()
+
+
+class PoolGroups:
+    """Sharing scope G (Sec. 5.4): the layers are cut into G groups over depth and every group has a
+    pool, a pool loss and a weight gradient of its own.  One PoolStep per group; a step runs them one
+    after the other (group g's weights are w_gate_up[g], w_down[g])."""
+
+    def __init__(self, G, T, d_model, d_ff, E, k, L, dtype, c, eps, alpha_pool, device="cuda:0", **kw):
+        assert L % G == 0, "groups hold the same number of layers"
+        self.G, self.Lg = G, L // G
+        self.groups = [PoolStep(T, d_model, d_ff, E, k, self.Lg, dtype, c, eps, alpha_pool, device=device, **kw)
+                       for _ in range(G)]
+
+    def step(self, xs, w_routers, sigmas, w_gate_up, w_down, grad_outs):
+        for g, ps in enumerate(self.groups):
+            lo, hi = g * self.Lg, (g + 1) * self.Lg
+            ps.step(xs[lo:hi], w_routers[lo:hi], sigmas[lo:hi], w_gate_up[g], w_down[g], grad_outs[lo:hi])

@@ -1,6 +1,7 @@
 """GPU parity of the stateful micro-batch loop: the one-step-behind usage statistic (App. F) against
 the oracle's loop, its checkpoint, and the recompute mode (App. C), whose results must be bitwise
-those of the mode that keeps the activations."""
+those of the mode that keeps the activations; and of the sharing-scope variants of Sec. 5.4 (per-layer
+loss on the shared pool, pool groups over depth)."""
 import numpy as np
 import pytest
 
@@ -136,3 +137,75 @@ def test_lagged_loop_against_the_oracle(name):
     torch.cuda.synchronize()
     again = [ps2.loss, ps2.aux_coef, ps2.layers[0].d_w_router, ps2.layers[0].dx]
     assert all(torch.equal(a, b) for a, b in zip(got[2], again))
+
+
+@pytest.mark.parametrize("name", ["C1", "bf16-tiles", "bf16-skew"])
+def test_layer_aux_on_the_shared_pool(name):
+    """The ablation row 'shared pool + per-layer loss' (Eq. 3 per layer, Sec. 5.4)."""
+    import torch
+    from paper_2605_06665_amd.pipeline import PoolStep
+    c = oracle_case(name)
+    w = c["w"]
+    xs = [dev(x, w.dtype) for x in c["xs"]]
+    wrs = [dev(x, w.dtype) for x in c["wrs"]]
+    gs = [dev(x, w.dtype) for x in c["gs"]]
+    wgu, wd = dev(pack_gate_up(c["wg"], c["wu"]), w.dtype), dev(c["wd"], w.dtype)
+    ps = PoolStep(w.T, w.d, w.f, w.E, w.k, w.L, _act(w), w.c, w.eps, w.alpha, aux="layer")
+    ps.step(xs, wrs, c["sigmas"], wgu, wd, gs)
+    torch.cuda.synchronize()
+    idxs = []
+    for l in range(w.L):
+        z = O.router_logits(c["xs"][l], c["wrs"][l])
+        ref_idx = O.topk_select(z, w.k)
+        gi = host(ps.layers[l].topk_idx)
+        tie = near_tie_tokens(z, w.k)
+        assert np.array_equal(gi[~tie], ref_idx[~tie])
+        ref_idx[tie] = gi[tie]
+        idxs.append(ref_idx)
+    ref = O.pool_step(c["xs"], c["wrs"], c["wg"], c["wu"], c["wd"], c["gs"], w.k, c["sigmas"], w.c, w.eps,
+                      w.alpha, idxs=idxs, aux="layer")
+    tol = TOL[w.dtype]
+    assert rel_err(host(ps.loss_layers), np.array(ref["loss_layers"])) <= 1e-4
+    assert rel_err(host(ps.aux_coef_layers), ref["coef"]) <= 1e-5
+    for l in range(w.L):
+        assert rel_err(host(ps.layers[l].d_w_router), ref["bw"][l]["dw_router"]) <= tol, l
+        assert rel_err(host(ps.layers[l].dx), ref["bw"][l]["dx"]) <= tol, l
+    assert rel_err(host(ps.d_w_gate_up), np.concatenate([ref["dw_gate"], ref["dw_up"]], axis=1)) <= tol
+
+
+@pytest.mark.parametrize("name", ["C1", "bf16-skew"])
+def test_sharing_scope_two_groups(name):
+    """G = 2 over the case's two layers: private pools, Eq. 3 per layer, no gradient across groups."""
+    import torch
+    from paper_2605_06665_amd.pipeline import PoolGroups
+    c = oracle_case(name)
+    w = c["w"]
+    assert w.L == 2
+    w2 = w.scaled(seed=w.seed + 1000)
+    pools = [(c["wg"], c["wu"], c["wd"]), W.gen_pool_weights(w2)]
+    xs = [dev(x, w.dtype) for x in c["xs"]]
+    wrs = [dev(x, w.dtype) for x in c["wrs"]]
+    gs = [dev(x, w.dtype) for x in c["gs"]]
+    wgu = [dev(pack_gate_up(p[0], p[1]), w.dtype) for p in pools]
+    wd = [dev(p[2], w.dtype) for p in pools]
+    pg = PoolGroups(2, w.T, w.d, w.f, w.E, w.k, w.L, _act(w), w.c, w.eps, w.alpha)
+    pg.step(xs, wrs, c["sigmas"], wgu, wd, gs)
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    groups = []
+    for g in range(2):
+        z = O.router_logits(c["xs"][g], c["wrs"][g])
+        ref_idx = O.topk_select(z, w.k)
+        gi = host(pg.groups[g].layers[0].topk_idx)
+        tie = near_tie_tokens(z, w.k)
+        assert np.array_equal(gi[~tie], ref_idx[~tie])
+        ref_idx[tie] = gi[tie]
+        r = O.pool_step([c["xs"][g]], [c["wrs"][g]], *pools[g], [c["gs"][g]], w.k, [c["sigmas"][g]], w.c, w.eps,
+                        w.alpha, idxs=[ref_idx])
+        groups.append(r)
+        ps = pg.groups[g]
+        assert abs(float(host(ps.loss)[0]) - r["loss"]) <= 1e-4 * abs(r["loss"])
+        assert rel_err(host(ps.layers[0].d_w_router), r["bw"][0]["dw_router"]) <= tol
+        assert rel_err(host(ps.layers[0].dx), r["bw"][0]["dx"]) <= tol
+        assert rel_err(host(ps.d_w_gate_up), np.concatenate([r["dw_gate"], r["dw_up"]], axis=1)) <= tol
+        assert rel_err(host(ps.d_w_down), r["dw_down"]) <= tol

@@ -1,7 +1,9 @@
 """Pins for the oracle's one-step-behind micro-batch loop (App. F) and for the recompute half of
 the expert FFN (App. C).  None of them calls the function under test to make its own expectation:
 the lagged statistic is counted by hand with Python loops, the gradients come from central finite
-differences of the float64 objective, the recompute is compared with a dense per-row evaluation."""
+differences of the float64 objective, the recompute is compared with a dense per-row evaluation.
+The sharing-scope variants of Sec. 5.4 (per-layer loss on a shared pool, pool groups) are pinned by
+a hand evaluation of Eq. 3 and finite differences."""
 import numpy as np
 import pytest
 
@@ -116,3 +118,79 @@ def test_recompute_matches_dense_rows():
             assert a[row, n] == pytest.approx(aa, rel=1e-12, abs=1e-14)
             assert b[row, n] == pytest.approx(bb, rel=1e-12, abs=1e-14)
             assert h[row, n] == pytest.approx(aa / (1.0 + np.exp(-aa)) * bb, rel=1e-12, abs=1e-14)
+
+
+# --------------------------------------------------------------------------- sharing scope, layer aux
+def _hand_layer_loss(x, wr, sigma, k, E):
+    """Eq. 3 for one layer with Python loops: alpha-free  E * sum_i f_i P_i."""
+    z = x @ wr.T
+    T = z.shape[0]
+    f = [0.0] * E
+    P = [0.0] * E
+    for t in range(T):
+        order = sorted(range(E), key=lambda i: (-z[t, i], i))
+        for i in order[:k]:
+            f[i] += 1.0 / (T * k)
+        nrm = float(np.sqrt(sum(z[t, i] ** 2 for i in range(E)))) + HP["eps"]
+        for i in range(E):
+            P[i] += sigma * HP["c"] * max(z[t, i] / nrm, 0.0) / T
+    return E * sum(fi * pi for fi, pi in zip(f, P)), np.array(f)
+
+
+def test_layer_aux_on_a_shared_pool():
+    batches, (wrs, wg, wu, wd, sigmas) = _batches(1, 120)
+    xs, gs = batches[0]
+    E, L, T = wg.shape[0], len(wrs), xs[0].shape[0]
+    res = O.pool_step(xs, wrs, wg, wu, wd, gs, HP["k"], sigmas, HP["c"], HP["eps"], HP["alpha"], aux="layer")
+    total = 0.0
+    for l in range(L):
+        hand, f = _hand_layer_loss(xs[l], wrs[l], sigmas[l], HP["k"], E)
+        assert res["loss_layers"][l] == pytest.approx(HP["alpha"] * hand, rel=1e-12)
+        assert np.allclose(res["coef"][l], HP["alpha"] * E * f / T, rtol=1e-12, atol=0)
+        total += HP["alpha"] * hand
+    assert res["loss"] == pytest.approx(total, rel=1e-12)
+    # gradient of the summed per-layer losses, f^(l) held constant, by central differences
+    fl = [res["fbar"][l].copy() for l in range(L)]
+
+    def lam():
+        tot = 0.0
+        for l in range(L):
+            fw = O.moe_layer_fwd(xs[l], wrs[l], wg, wu, wd, HP["k"], sigmas[l], HP["c"], HP["eps"])
+            tot += float(np.sum(fw["out"] * gs[l])) + HP["alpha"] * E * float(np.sum(fl[l] * fw["psum"] / T))
+        return tot
+
+    rng = np.random.default_rng(9)
+    for l in range(L):
+        grad = res["bw"][l]["dw_router"]
+        scale = np.max(np.abs(grad))
+        for _ in range(10):
+            index = tuple(int(rng.integers(0, n)) for n in wrs[l].shape)
+            num = _fd(lam, wrs[l], index)
+            assert abs(num - grad[index]) <= 2e-7 * scale + 1e-9
+
+
+def test_sharing_scope_groups():
+    (xs, gs), = _batches(1, 140)[0]
+    _, (wrs, wg, wu, wd, sigmas) = _batches(1, 140)
+    L = len(wrs)
+    # G = 1: the group step is the pool step
+    one = dict(xs=xs, w_routers=wrs, w_gate=wg, w_up=wu, w_down=wd, grad_outs=gs, sigmas=sigmas)
+    res, total = O.pool_groups_step([one], HP["k"], HP["c"], HP["eps"], HP["alpha"])
+    ref = O.pool_step(xs, wrs, wg, wu, wd, gs, HP["k"], sigmas, HP["c"], HP["eps"], HP["alpha"])
+    assert total == ref["loss"] and np.array_equal(res[0]["dw_gate"], ref["dw_gate"])
+    # one layer per group, private pools: Eq. 3 per layer, and no gradient crosses the groups
+    rng = np.random.default_rng(1)
+    pools = [(wg, wu, wd)] + [tuple(rng.standard_normal(w.shape) * 0.4 for w in (wg, wu, wd)) for _ in range(L - 1)]
+    groups = [dict(xs=[xs[l]], w_routers=[wrs[l]], w_gate=pools[l][0], w_up=pools[l][1], w_down=pools[l][2],
+                   grad_outs=[gs[l]], sigmas=[sigmas[l]]) for l in range(L)]
+    res, total = O.pool_groups_step(groups, HP["k"], HP["c"], HP["eps"], HP["alpha"])
+    E = wg.shape[0]
+    hand_total = 0.0
+    for l in range(L):
+        hand, _ = _hand_layer_loss(xs[l], wrs[l], sigmas[l], HP["k"], E)
+        assert res[l]["loss"] == pytest.approx(HP["alpha"] * hand, rel=1e-12)
+        hand_total += HP["alpha"] * hand
+        # a private pool's weight gradient is that of a dense sum over this layer's tokens only
+        out = O.moe_layer_fwd(xs[l], wrs[l], *pools[l], HP["k"], sigmas[l], HP["c"], HP["eps"])
+        assert np.array_equal(out["counts"], res[l]["counts"][0])
+    assert total == pytest.approx(hand_total, rel=1e-12)
