@@ -174,8 +174,8 @@ constexpr int kSchedBase = 16;
 __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restrict__ offsets, int E,
                                                           int total_rows, int BM,
                                                           int32_t* __restrict__ meta) {
-    __shared__ int lrows[512];            // rows per expert (0 past E)
-    __shared__ int lkey[512];             // place of an expert in the dealt order (a permutation)
+    __shared__ __attribute__((aligned(16))) int lrows[512];   // rows per expert (0 past E)
+    __shared__ __attribute__((aligned(16))) int lkey[512];    // place of an expert in the dealt order
     __shared__ int ltiles[512];           // tiles of the expert at a given place
     __shared__ int scan[2][512];
     const int t = threadIdx.x;
@@ -192,19 +192,31 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
     // is laid out for them: experts sorted by rows, descending, are dealt to the eight parts in
     // serpentine order (0..7, 7..0, ...), which gives every XCD the same amount of work to within
     // one small expert and makes the tiles that run at the same time equally long.
+    // (entries past E hold no rows and take no part; the loops read four experts per LDS access)
+    const int E4 = (E + 3) / 4;
+    const int rt = r1 - r0;
     int rank = 0;                         // experts with more rows (ties: lower index first)
-    for (int o = 0; o < 512; o++) {
-        const int ro = lrows[o], rt = r1 - r0;
-        rank += (ro > rt) || (ro == rt && o < t);
+    for (int o4 = 0; o4 < E4; o4++) {
+        const int4 v = reinterpret_cast<const int4*>(lrows)[o4];
+        const int o = 4 * o4;
+        rank += (v.x > rt) || (v.x == rt && o < t);
+        rank += (v.y > rt) || (v.y == rt && o + 1 < t);
+        rank += (v.z > rt) || (v.z == rt && o + 2 < t);
+        rank += (v.w > rt) || (v.w == rt && o + 3 < t);
     }
     const int lap = rank / kNumXcd, posn = rank % kNumXcd;
     const int part = (lap & 1) ? kNumXcd - 1 - posn : posn;
-    const int place = part * (512 / kNumXcd) + lap;     // unique: lap < 64
+    const int place = t < E ? part * (512 / kNumXcd) + lap : 0x7fffffff;     // unique below E: lap < 64
     lkey[t] = place;
+    ltiles[t] = 0;
     __syncthreads();
     int dense = 0;                        // experts placed before this one
-    for (int o = 0; o < 512; o++) dense += lkey[o] < place;
-    ltiles[dense] = nt;
+    for (int o4 = 0; o4 < E4; o4++) {
+        const int4 v = reinterpret_cast<const int4*>(lkey)[o4];
+        dense += (v.x < place) + (v.y < place) + (v.z < place) + (v.w < place);
+    }
+    __syncthreads();
+    if (t < E) ltiles[dense] = nt;
     __syncthreads();
     // exclusive prefix sum of the tiles in list order (inclusive Hillis-Steele scan over 512 entries)
     const int mine = ltiles[t];
