@@ -26,7 +26,9 @@ closed forms (uniform usage, single expert, L = 1 reducing to Eq. 3, Eq. 6
 identity), central finite differences for every gradient, E = 1 reducing to a
 dense SwiGLU MLP; the one-step-behind loop against a hand count of the previous
 micro-batch's slots and finite differences of the lagged objective; the
-recompute half against the forward record.  `estimate_c` (App. G, Alg. 1) is pinned only statistically.
+recompute half against the forward record.  `c_from_samples` (App. G, Alg. 1) is pinned by
+loops on small draws and closed cases, `estimate_c` statistically; `distinct_experts`
+(App. D) by hand cases and the occupancy closed form for uniform routing.
 """
 from __future__ import annotations
 
@@ -413,14 +415,33 @@ def objective(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps,
 # ---------------------------------------------------------------------------
 # App. G, Alg. 1: Monte-Carlo estimate of the NormRouter constant c
 # ---------------------------------------------------------------------------
-def estimate_c(E, k, n_samples=100_000, seed=0):
-    """c = mean of 1 / || top-k( relu(x/||x||) ) ||_2 over x ~ N(0, I_E).
-    Samples whose top-k part is all zero (1/0) are dropped; the paper does not
-    treat that case.  Returns (c, samples_used)."""
-    rng = np.random.default_rng(seed)
-    x = rng.standard_normal((n_samples, E))
+def c_from_samples(samples, k):
+    """App. G, Alg. 1 on given draws x ~ N(0, I_E), one per row: for every row
+    y = relu(x / ||x||_2), the k largest components of y, 1 / their 2-norm; c is the mean.
+    Rows whose top-k part is all zero (1/0) are dropped; the paper does not treat that
+    case.  Returns (c, rows_used)."""
+    x = np.asarray(samples, F64)
     y = np.maximum(0.0, x / np.linalg.norm(x, axis=1, keepdims=True))
     ysort = -np.sort(-y, axis=1)
     nrm = np.sqrt(np.sum(ysort[:, :k] ** 2, axis=1))
     ok = nrm > 0.0
     return float(np.mean(1.0 / nrm[ok])), int(ok.sum())
+
+
+def estimate_c(E, k, n_samples=100_000, seed=0):
+    """Alg. 1 with its own draws.  Returns (c, samples_used)."""
+    rng = np.random.default_rng(seed)
+    return c_from_samples(rng.standard_normal((n_samples, E)), k)
+
+
+# ---------------------------------------------------------------------------
+# App. D: distinct experts touched by a token over the layers that share a pool
+# ---------------------------------------------------------------------------
+def distinct_experts(idx_layers):
+    """U(x) = | { experts selected for token x at any of the L layers } |  (App. D; stated
+    there for top-1, taken here over all k selections of every layer).
+    idx_layers: L arrays [T, k].  Returns (U [T] int64, mean of U)."""
+    idx = np.stack([np.asarray(i) for i in idx_layers], axis=1)      # [T, L, k]
+    T = idx.shape[0]
+    U = np.array([len(set(idx[t].ravel().tolist())) for t in range(T)], dtype=np.int64)
+    return U, float(U.mean())
