@@ -153,6 +153,35 @@ def main():
         wg_tflops = gemm_flops_third * w.L * a.steps / (t_wg_ms * 1e-3) / 1e12
         others["wgrad_pool"] = {"TFLOP/s": wg_tflops, "frac": wg_tflops / PEAK_BF16_TFLOPS}
 
+    # ---- analysis observables (outside the timed step): Alg. 1 on 1e5 draws, distinct experts per token
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    n_draws = 100000
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    draws = torch.randn((n_draws, w.E), generator=gen, device=dev, dtype=torch.float32)
+    c_out = torch.zeros(1, dtype=torch.float32, device=dev)
+    c_used = torch.zeros(1, dtype=torch.int32, device=dev)
+    ms_c = timed(lambda: U.estimate_c(w.E, w.k, draws, c_out, c_used, ps.ws))
+    idx_tab = torch.tensor([st.topk_idx.data_ptr() for st in ps.layers], dtype=torch.int64, device=dev)
+    dist = torch.zeros(w.T, dtype=torch.int32, device=dev)
+    dist_mean = torch.zeros(1, dtype=torch.float32, device=dev)
+    ms_u = timed(lambda: U.distinct_experts(ps.shape(1.0), w.L, idx_tab, dist, dist_mean, ps.ws))
+    by_c, by_u = 4.0 * n_draws * w.E, 4.0 * w.L * w.T * w.k + 4.0 * w.T
+    others["estimate_c"] = {"GB/s": by_c / (ms_c * 1e-3) / 1e9, "frac": by_c / (ms_c * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                            "avg_ms": ms_c, "algorithmic_bytes": by_c, "draws": n_draws, "c": float(c_out.item())}
+    others["distinct_experts"] = {"GB/s": by_u / (ms_u * 1e-3) / 1e9, "frac": by_u / (ms_u * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                  "avg_ms": ms_u, "algorithmic_bytes": by_u,
+                                  "mean_distinct_per_token": float(dist_mean.item())}
+
     out = {
         "metric": "shared-pool MoE layer fwd+bwd tokens/s; grouped-GEMM % bf16 MFMA peak",
         "value": w.L * w.T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,

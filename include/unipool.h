@@ -223,6 +223,33 @@ int unipool_pool_aux_loss(const unipool_shape* shape, const int32_t* counts, con
                           const float* fbar_in, int32_t* pool_counts, float* fbar_out,
                           float* loss, float* aux_coef, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Monte-Carlo estimate of the NormRouter calibration constant c (App. G, Alg. 1) from draws
+ * the caller supplies: for every row x of samples, y = relu(x / ||x||_2), the k largest
+ * components of y, 1 / their 2-norm; c is the mean over the rows.  A row without a positive
+ * component has an all-zero top-k part and is left out (the paper does not treat 1/0);
+ * samples_used tells how many rows entered.  Float arithmetic, fixed summation order
+ * (bitwise repeatable); the final mean is taken in double.
+ * in : samples [n_samples, E] float (device), meant to be N(0, 1) draws;  1 <= k <= min(8, E);
+ *      E <= 512.
+ * out: c_out [1] float;  samples_used [1] int32.
+ * workspace: at least 2 * roundup256(4 * ceil(n_samples / 64)) bytes, 256-byte aligned.
+ */
+int unipool_estimate_c(int E, int k, const float* samples, int n_samples, float* c_out,
+                       int32_t* samples_used, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Distinct pool experts per token (App. D): U(t) = number of different experts token t
+ * selects over n_layers layers that route into one pool (all k selections of a layer count;
+ * the paper states it for top-1), and its mean over the tokens.
+ * in : topk_idx_l: device array of n_layers device pointers, each to a [T, k] int32 tensor
+ *      (as written by unipool_route).
+ * out: distinct [T] int32;  mean_distinct [1] float.
+ */
+int unipool_distinct_experts(const unipool_shape* shape, int n_layers, const void* const* topk_idx_l,
+                             int32_t* distinct, float* mean_distinct,
+                             void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,7 +29,8 @@ class Shape(ctypes.Structure):
 ENTRY_POINTS = ("unipool_workspace_bytes", "unipool_last_error", "unipool_version", "unipool_route",
                 "unipool_route_bwd", "unipool_permute", "unipool_expert_ffn_fwd",
                 "unipool_expert_ffn_recompute", "unipool_expert_ffn_bwd", "unipool_expert_wgrad", "unipool_combine",
-                "unipool_combine_bwd", "unipool_pool_aux_loss")
+                "unipool_combine_bwd", "unipool_pool_aux_loss", "unipool_estimate_c",
+                "unipool_distinct_experts")
 
 
 def lib_path() -> str:
@@ -64,6 +65,8 @@ def load_library():
             "unipool_combine": [SP] + [P] * 4 + [P, Z, P],
             "unipool_combine_bwd": [SP] + [P] * 6 + [P, Z, P],
             "unipool_pool_aux_loss": [SP] + [P] * 7 + [P, Z, P],
+            "unipool_estimate_c": [I, I, P, I, P, P, P, Z, P],
+            "unipool_distinct_experts": [SP, I, P, P, P, P, Z, P],
         }
         for name, argtypes in sigs.items():
             fn = getattr(lib, name)
@@ -203,3 +206,18 @@ def pool_aux_loss(shape, counts, psum, fbar_in, pool_counts, fbar_out, loss, aux
                                                 _ptr(fbar_in), _ptr(pool_counts), _ptr(fbar_out),
                                                 _ptr(loss), _ptr(aux_coef), p, n, _stream(stream)),
            "unipool_pool_aux_loss")
+
+
+def estimate_c(E, k, samples, c_out, samples_used, ws, stream=None):
+    """samples: [n, E] float32 device tensor of N(0, 1) draws; c_out [1] float32; samples_used [1] int32."""
+    p, n = _ws(ws)
+    _check(load_library().unipool_estimate_c(int(E), int(k), _ptr(samples), int(samples.shape[0]), _ptr(c_out),
+                                             _ptr(samples_used), p, n, _stream(stream)), "unipool_estimate_c")
+
+
+def distinct_experts(shape, n_layers, topk_idx_tab, distinct, mean_distinct, ws, stream=None):
+    """topk_idx_tab: int64 device tensor holding n_layers device addresses of [T, k] int32 tensors."""
+    p, n = _ws(ws)
+    _check(load_library().unipool_distinct_experts(ctypes.byref(shape), int(n_layers), _ptr(topk_idx_tab),
+                                                   _ptr(distinct), _ptr(mean_distinct), p, n, _stream(stream)),
+           "unipool_distinct_experts")

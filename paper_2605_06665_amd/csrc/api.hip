@@ -12,6 +12,9 @@ namespace {
 thread_local char g_err[512] = "no error";
 
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+}  // namespace
+size_t align_up_256(size_t v) { return (v + 255) & ~(size_t)255; }
+namespace {
 
 // UNIPOOL_FORCE_NAIVE=1 sends bfloat16 contractions to the plain one-thread-per-element kernels
 // (a debugging aid; still device code).
@@ -350,6 +353,44 @@ int unipool_pool_aux_loss(const unipool_shape* shape, const int32_t* counts, con
     return check_hip(launch_pool_aux_loss(*shape, counts, psum, fbar_in, pool_counts, fbar_out, loss,
                                           aux_coef, (hipStream_t)stream),
                      "unipool_pool_aux_loss");
+}
+
+int unipool_estimate_c(int E, int k, const float* samples, int n_samples, float* c_out,
+                       int32_t* samples_used, void* ws, size_t ws_bytes, void* stream) {
+    if (E < 1 || E > unipool::kMaxE)
+        return unipool::set_error(UNIPOOL_EINVAL, "%s: E=%d outside [1, %d]", __func__, E, unipool::kMaxE);
+    if (k < 1 || k > unipool::kMaxK || k > E)
+        return unipool::set_error(UNIPOOL_EINVAL, "%s: k=%d outside [1, min(%d, E=%d)]", __func__, k,
+                                  unipool::kMaxK, E);
+    if (n_samples < 1) return unipool::set_error(UNIPOOL_EINVAL, "%s: n_samples=%d must be positive", __func__, n_samples);
+    REQUIRE_PTR(samples); REQUIRE_PTR(c_out); REQUIRE_PTR(samples_used);
+    const size_t nb = (size_t)unipool::c_blocks(n_samples);
+    const size_t need = 2 * unipool::align_up_256(nb * 4);
+    if (!ws) return unipool::set_error(UNIPOOL_EWORKSPACE, "%s: workspace is NULL", __func__);
+    if (((uintptr_t)ws & 255) != 0)
+        return unipool::set_error(UNIPOOL_EWORKSPACE, "%s: workspace is not 256-byte aligned", __func__);
+    if (ws_bytes < need)
+        return unipool::set_error(UNIPOOL_EWORKSPACE, "%s: workspace has %zu bytes, %zu needed", __func__, ws_bytes, need);
+    float* part_sum = (float*)ws;
+    int32_t* part_used = (int32_t*)((char*)ws + unipool::align_up_256(nb * 4));
+    return unipool::check_hip(unipool::launch_estimate_c(E, k, samples, n_samples, part_sum, part_used, c_out,
+                                                         samples_used, (hipStream_t)stream),
+                              "unipool_estimate_c");
+}
+
+int unipool_distinct_experts(const unipool_shape* shape, int n_layers, const void* const* topk_idx_l,
+                             int32_t* distinct, float* mean_distinct, void* ws, size_t ws_bytes,
+                             void* stream) {
+    PROLOGUE();
+    if (n_layers < 1) return set_error(UNIPOOL_EINVAL, "%s: n_layers=%d must be positive", __func__, n_layers);
+    REQUIRE_PTR(topk_idx_l); REQUIRE_PTR(distinct); REQUIRE_PTR(mean_distinct);
+    NEED_WS();
+    // the block sums (T / 256 words) live in the router's partial-sum area
+    const WsLayout w = ws_layout(*shape);
+    return check_hip(launch_distinct_experts((const int32_t* const*)topk_idx_l, n_layers, shape->T, shape->k,
+                                             distinct, (int32_t*)((char*)ws + w.psum_part), mean_distinct,
+                                             (hipStream_t)stream),
+                     "unipool_distinct_experts");
 }
 
 }  // extern "C"

@@ -33,6 +33,13 @@ hipError_t launch_pool_aux_loss(const unipool_shape& s, const int32_t* counts, c
                                 const float* fbar_in, int32_t* pool_counts, float* fbar_out,
                                 float* loss, float* aux_coef, hipStream_t st);
 
+// ---- analysis.hip -----------------------------------------------------------------
+int c_blocks(int n);     // partial sums the c estimate needs for n draws
+hipError_t launch_estimate_c(int E, int k, const float* samples, int n, float* part_sum,
+                             int32_t* part_used, float* c_out, int32_t* used_out, hipStream_t st);
+hipError_t launch_distinct_experts(const int32_t* const* idx_layers, int L, int T, int k,
+                                   int32_t* distinct, int32_t* part_sum, float* mean_out, hipStream_t st);
+
 // ---- gemm_naive.hip: one thread per output element; any shape, both dtypes ---------
 hipError_t naive_logits(const unipool_shape& s, const void* x, const void* w, float* z, hipStream_t st);
 hipError_t naive_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
