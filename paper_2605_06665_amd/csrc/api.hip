@@ -27,6 +27,16 @@ bool force_naive() {
     return v == 1;
 }
 
+// UNIPOOL_UNFUSED_ROUTER=1 keeps the logits GEMM and the selection in separate kernels.
+bool unfused_router() {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("UNIPOOL_UNFUSED_ROUTER");
+        v = (e && e[0] == '1') ? 1 : 0;
+    }
+    return v == 1;
+}
+
 __global__ void fill_zero_kernel(uint32_t* p, size_t words) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < words) p[i] = 0u;
@@ -161,6 +171,15 @@ int unipool_route(const unipool_shape* shape, const void* x, const void* w_route
     hipStream_t st = (hipStream_t)stream;
     float* z = logits ? logits : (float*)(base + w.dz);
     hipError_t e;
+    if (mfma_route_fused_supported(*shape) && !force_naive() && !unfused_router()) {
+        // logits, scores, top-k and block statistics in one kernel; then the sum over the blocks
+        int32_t* cnt_part = (int32_t*)(base + w.dsigma_part);
+        float* psum_part = (float*)(base + w.psum_part);
+        e = mfma_route_fused(*shape, x, w_router, z, topk_idx, topk_gate, cnt_part, psum_part, st);
+        if (e != hipSuccess) return check_hip(e, "unipool_route: fused router");
+        return check_hip(launch_route_finalize(*shape, cnt_part, psum_part, counts, psum, st),
+                         "unipool_route: statistics");
+    }
     if (mfma_router_supported(*shape) && !force_naive())
         e = mfma_logits(*shape, x, w_router, z, (int32_t*)(base + w.tile_meta), st);
     else

@@ -27,6 +27,7 @@
 #include <type_traits>
 
 #include "kernels.h"
+#include "route_select.h"
 
 namespace unipool {
 
@@ -36,6 +37,7 @@ constexpr int EPI_STORE = 0;       // bf16 store (optionally added to the destin
 constexpr int EPI_SWIGLU_FWD = 1;  // tile = [gate | up] columns; writes A, B, H = silu(A)*B
 constexpr int EPI_SWIGLU_BWD = 2;  // acc = dH; reads A, B; writes dA | dB
 constexpr int EPI_F32 = 3;         // float store
+constexpr int EPI_ROUTE = 4;       // acc = logits: float store, then NormRouter scores, top-k and statistics
 
 constexpr int kNumXcd = 8;
 
@@ -84,7 +86,25 @@ struct GemmArgs {
     int up_rows;          // EPI_SWIGLU_FWD: row offset of the up projection inside W_e (= d_ff)
     int group_m;          // row tiles walked together
     const void* zeros;    // >= 16 readable zero bytes (reduction tail of KTAIL kernels)
+    // ungrouped matrices (router): flat_rows > 0 replaces the tile table by row tiles of flat_bm rows
+    int flat_rows, flat_bm;
+    // EPI_ROUTE: outputs of the selection and its constants
+    int32_t* topk_idx;
+    float* topk_gate;
+    int32_t* cnt_part;
+    float* psum_part;
+    int topk;
+    float sigma_c, eps;
 };
+
+// EPI_ROUTE keeps the float logits of a tile of up to 128 tokens in LDS: rows of kRouteLdz floats,
+// then the score sums of the eight wavefronts and the selection counts of the two 64-token blocks.
+constexpr int kRouteRows = 128;
+constexpr int kRouteMaxE = 256;
+constexpr int kRouteLdz = kRouteMaxE + 4;
+constexpr int kRoutePsOff = kRouteRows * kRouteLdz * 4;
+constexpr int kRouteCntOff = kRoutePsOff + 8 * kRouteMaxE * 4;
+static_assert(kRouteCntOff + 2 * kRouteMaxE * 4 <= 160 * 1024, "router tile and statistics fit LDS");
 
 // ---------------------------------------------------------------------------------------------
 // low-level helpers
@@ -284,7 +304,7 @@ template <int EPI> struct Staging {
     static constexpr int SROW = SC * 2 + 16;                    // row stride in bytes
     static constexpr int WSTG = (EPI == EPI_SWIGLU_BWD ? 2 : 1) * 32 * SROW;   // bytes per wavefront
     static constexpr int RW = 32768 / WSTG < kXwWaves ? 32768 / WSTG : kXwWaves;
-    static constexpr int REGIONS = EPI == EPI_F32 ? 0 : (kXwWaves + RW - 1) / RW;
+    static constexpr int REGIONS = (EPI == EPI_F32 || EPI == EPI_ROUTE) ? 0 : (kXwWaves + RW - 1) / RW;
     static constexpr bool PREW1 = REGIONS <= 2;
     static_assert(REGIONS <= 3, "three operand buffers are free in the epilogue");
 };
@@ -580,7 +600,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     // The buffers of the last stage become the staging space of the epilogue; the others take the
     // first stages of the next tile now, so that its pipeline is full when the epilogue ends.
     constexpr bool PREW1 = Staging<EPI>::PREW1;
-    if constexpr (!KTAIL) {
+    if constexpr (!KTAIL && EPI != EPI_ROUTE) {
         if (nxt.valid) {
             set_sources(nxt.expert, nxt.row0, nxt.rows, nxt.nt);
 #pragma unroll
@@ -603,7 +623,25 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     const int lrow = lane & 31;
     const int lhalf = lane >> 5;
 
-    if constexpr (EPI == EPI_F32) {
+    if constexpr (EPI == EPI_ROUTE) {
+        // the logits of the tile go to LDS in float; the selection follows once all wavefronts are done
+        float* tile = reinterpret_cast<float*>(smem);
+#pragma unroll
+        for (int tm = 0; tm < MTV; tm++) {
+            const int r_in = (wm + 2 * tm) * 32 + lrow;
+            if (r_in < kRouteRows) {
+#pragma unroll
+                for (int tn = 0; tn < TN; tn++)
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const int col = wpos[tn] + 8 * q + 4 * lhalf;
+                        *reinterpret_cast<float4*>(tile + r_in * kRouteLdz + col) =
+                            make_float4(acc[tm][tn][4 * q], acc[tm][tn][4 * q + 1], acc[tm][tn][4 * q + 2],
+                                        acc[tm][tn][4 * q + 3]);
+                    }
+            }
+        }
+    } else if constexpr (EPI == EPI_F32) {
         float* out = reinterpret_cast<float*>(g.out0);
 #pragma unroll
         for (int tm = 0; tm < MTV; tm++) {
@@ -770,6 +808,64 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
 #undef UNIPOOL_LOAD_AB1
 }
 
+// Second half of EPI_ROUTE, run by all wavefronts once the tile's logits are in LDS: logits to
+// global memory as whole rows, then per token norm, scores, top-k and gates (the stand-alone top-k
+// kernel's code and token-to-wavefront assignment: wavefront w owns tokens 16w .. 16w+15 of the
+// tile, four wavefronts make one 64-token block of the statistics).
+template <int GS, int VPL>
+__device__ __forceinline__ void route_epilogue(const GemmArgs& g, char* smem, const TileRef& cur) {
+    constexpr int TPW = 64 / GS;
+    const float* tile = reinterpret_cast<const float*>(smem);
+    float* lds_ps = reinterpret_cast<float*>(smem + kRoutePsOff);
+    int* lds_cnt = reinterpret_cast<int*>(smem + kRouteCntOff);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = lane / GS, sl = lane % GS;
+    const int E = g.N, rows = cur.rows, row0 = cur.row0;
+    for (int i = tid; i < 2 * kRouteMaxE; i += kXwThreads) lds_cnt[i] = 0;
+    float* zout = reinterpret_cast<float*>(g.out0);
+    const int c4n = E / 4;                                 // E is a multiple of 8 here
+    for (int id = tid; id < rows * c4n; id += kXwThreads) {
+        const int r = id / c4n, c4 = id % c4n;
+        *reinterpret_cast<float4*>(zout + (size_t)(row0 + r) * g.ldo + 4 * c4) =
+            *reinterpret_cast<const float4*>(tile + r * kRouteLdz + 4 * c4);
+    }
+    lds_barrier();
+    float ps[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; i++) ps[i] = 0.f;
+    for (int tt = 0; tt < 16; tt += TPW) {
+        const int lr = wave * 16 + tt + grp;
+        const float* zr = tile + min(lr, rows - 1) * kRouteLdz;
+        float z[VPL];
+#pragma unroll
+        for (int i = 0; i < VPL; i++) {
+            const int e = sl + GS * i;
+            z[i] = (e < E) ? zr[e] : 0.f;
+        }
+        route_select<GS, VPL>(z, sl, E, g.topk, g.sigma_c, g.eps, lr < rows, (size_t)(row0 + lr), g.topk_idx,
+                              g.topk_gate, lds_cnt + (wave >> 2) * kRouteMaxE, ps);
+    }
+#pragma unroll
+    for (int i = 0; i < VPL; i++) {
+#pragma unroll
+        for (int o = GS; o < 64; o <<= 1) ps[i] += __shfl_xor(ps[i], o, 64);
+        if (grp == 0 && sl + GS * i < kRouteMaxE) lds_ps[wave * kRouteMaxE + sl + GS * i] = ps[i];
+    }
+    lds_barrier();
+    const int nblocks = (g.flat_rows + 63) / 64;
+    const int e = tid & (kRouteMaxE - 1), half = tid >> 8;          // 512 threads: two blocks of 64 tokens
+    const int blk = row0 / 64 + half;
+    if (e < E && blk < nblocks && half * 64 < rows) {
+        const float* p = lds_ps + (4 * half) * kRouteMaxE + e;
+        float v = p[0];
+        v += p[kRouteMaxE];
+        v += p[2 * kRouteMaxE];
+        v += p[3 * kRouteMaxE];
+        g.psum_part[(size_t)blk * E + e] = v;
+        g.cnt_part[(size_t)blk * E + e] = lds_cnt[half * kRouteMaxE + e];
+    }
+}
+
 template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL>
 __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -786,8 +882,9 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
     //     so that no workgroup keeps the same position inside the experts' tile groups.  The tile
     //     table lists the experts of a part in descending order of rows: the workgroups of an XCD
     //     work on tiles of nearly equal length at any time and end together.
-    const int n_mt = g.tile_meta[0];
-    const int G = g.group_m;
+    const bool flat = g.flat_rows > 0;
+    const int n_mt = flat ? (g.flat_rows + g.flat_bm - 1) / g.flat_bm : g.tile_meta[0];
+    const int G = flat ? 1 : g.group_m;
     const int per_group = G * g.n_tiles_n;
     const int total = ((n_mt + G - 1) / G) * per_group;
     const int per_xcd = (total + kNumXcd - 1) / kNumXcd;
@@ -808,6 +905,13 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
             const int rem = lt % per_group;
             const int mt = grp * G + rem % G;
             if (mt >= n_mt) continue;
+            if (flat) {
+                t.valid = 1;
+                t.row0 = mt * g.flat_bm;
+                t.rows = min(g.flat_bm, g.flat_rows - t.row0);
+                t.nt = rem;
+                return t;
+            }
             const int rows = g.tile_meta[kTileBase + 4 * mt + 2];
             if (rows <= 0) continue;
             t.valid = 1;
@@ -832,8 +936,13 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
             case 3: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 3>(g, smem, cur, nxt, pre, g0); break;
             default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4>(g, smem, cur, nxt, pre, g0); break;
         }
+        if constexpr (EPI == EPI_ROUTE) {
+            lds_barrier();            // the tile's logits are complete in LDS
+            if (g.N <= 128) route_epilogue<16, 8>(g, smem, cur);
+            else route_epilogue<16, 16>(g, smem, cur);
+        }
         lds_barrier();                // the staging space is free: the next tile may load into it
-        pre = (!KTAIL && nxt.valid) ? ((Staging<EPI>::PREW1 && nk > 1) ? 3 : 1) : 0;
+        pre = (!KTAIL && EPI != EPI_ROUTE && nxt.valid) ? ((Staging<EPI>::PREW1 && nk > 1) ? 3 : 1) : 0;
         g0 = (g0 + nk) % 6;           // the buffers repeat with period 2 and 3
         cur = nxt;
     }
@@ -1149,14 +1258,32 @@ bool mfma_router_supported(const unipool_shape& s) {
 
 hipError_t mfma_logits(const unipool_shape& s, const void* x, const void* w, float* z,
                        int32_t* tile_meta, hipStream_t st) {
-    hipError_t e = build_tiles(nullptr, 1, s.T, tile_meta, st);
-    if (e != hipSuccess) return e;
     GemmArgs a = {};
     a.X = (const bf16*)x; a.ldx = s.d_model;
     a.W = (const bf16*)w; a.w_stride = 0; a.ldw = s.d_model;
     a.K = s.d_model; a.N = s.E; a.n_tiles_n = cdiv(s.E, kBN);
     a.tile_meta = tile_meta; a.out0 = z; a.ldo = s.E;
+    a.flat_rows = s.T; a.flat_bm = kFlatBM;
     return run_xw<true, EPI_F32>(a, cdiv(s.T, kBM), st);
+}
+
+bool mfma_route_fused_supported(const unipool_shape& s) {
+    return mfma_router_supported(s) && s.E <= kRouteMaxE;
+}
+
+// Logits GEMM with the NormRouter selection in its epilogue: one tile = 128 tokens x all experts.
+hipError_t mfma_route_fused(const unipool_shape& s, const void* x, const void* w, float* z, int32_t* topk_idx,
+                            float* topk_gate, int32_t* cnt_part, float* psum_part, hipStream_t st) {
+    static_assert(kFlatBM == kRouteRows, "the router tile holds one flat tile");
+    GemmArgs a = {};
+    a.X = (const bf16*)x; a.ldx = s.d_model;
+    a.W = (const bf16*)w; a.w_stride = 0; a.ldw = s.d_model;
+    a.K = s.d_model; a.N = s.E; a.n_tiles_n = 1;
+    a.out0 = z; a.ldo = s.E;
+    a.flat_rows = s.T; a.flat_bm = kFlatBM;
+    a.topk_idx = topk_idx; a.topk_gate = topk_gate; a.cnt_part = cnt_part; a.psum_part = psum_part;
+    a.topk = s.k; a.sigma_c = s.sigma * s.c; a.eps = s.eps;
+    return run_xw<true, EPI_ROUTE>(a, cdiv(s.T, kBM), st);
 }
 
 hipError_t mfma_ffn_gate_up(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
@@ -1258,14 +1385,12 @@ hipError_t mfma_route_bwd_mm(const unipool_shape& s, const void* x, const void* 
     const size_t n = (size_t)E * d;
     reduce_partials_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(wpart, used, n, dw);
     // dx (+)= dz W   (W is [E][d]: reduction index strided)
-    int32_t* meta2 = tile_meta + 2048;
-    e = build_tiles(nullptr, 1, T, meta2, st);
-    if (e != hipSuccess) return e;
     GemmArgs b = {};
+    b.flat_rows = T; b.flat_bm = kFlatBM;
     b.X = (const bf16*)dz; b.ldx = E;
     b.W = (const bf16*)w; b.w_stride = 0; b.ldw = d;
     b.K = E; b.N = d; b.n_tiles_n = cdiv(d, kBN);
-    b.tile_meta = meta2; b.out0 = dx; b.ldo = d; b.add = dx_accumulate; b.zeros = zeros;
+    b.tile_meta = tile_meta; b.out0 = dx; b.ldo = d; b.add = dx_accumulate; b.zeros = zeros;
     if (E % kBK != 0) return run_xw<false, EPI_STORE, true>(b, cdiv(T, kBM), st);
     return run_xw<false, EPI_STORE>(b, cdiv(T, kBM), st);
 }

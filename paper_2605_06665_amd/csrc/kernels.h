@@ -11,6 +11,8 @@ hipError_t launch_route_score_topk(const unipool_shape& s, const float* logits, 
                                    float* topk_gate, int32_t* counts, float* psum,
                                    int32_t* cnt_part, float* psum_part, hipStream_t st);
 // Per-token backward of the score: writes dz (act dtype) and d_sigma.
+hipError_t launch_route_finalize(const unipool_shape& s, const int32_t* cnt_part, const float* psum_part,
+                                 int32_t* counts, float* psum, hipStream_t st);
 hipError_t launch_route_bwd_dz(const unipool_shape& s, const float* logits, const int32_t* topk_idx,
                                const float* dgate, const float* aux_coef, void* dz,
                                float* dsigma_part, float* d_sigma, hipStream_t st);
@@ -65,6 +67,9 @@ hipError_t mfma_logits(const unipool_shape& s, const void* x, const void* w, flo
 hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
                         const void* wgu, const void* wd, void* a, void* b, void* h, void* y,
                         int32_t* tile_meta, hipStream_t st);
+bool mfma_route_fused_supported(const unipool_shape& s);
+hipError_t mfma_route_fused(const unipool_shape& s, const void* x, const void* w, float* z, int32_t* topk_idx,
+                            float* topk_gate, int32_t* cnt_part, float* psum_part, hipStream_t st);
 hipError_t mfma_ffn_gate_up(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
                            const void* wgu, void* a, void* b, void* h, int32_t* tile_meta,
                            hipStream_t st);

@@ -2,6 +2,7 @@
 // statistics, and the backward of the score.  One 64-lane wavefront owns one token at a
 // time; lane j holds the logits of experts j, j+64, ... (at most 8 per lane, E <= 512).
 #include "kernels.h"
+#include "route_select.h"
 
 namespace unipool {
 
@@ -50,45 +51,7 @@ __global__ __launch_bounds__(256) void route_score_topk_kernel(
 #pragma unroll
         for (int i = 0; i < VPL; i++) z[i] = zn[i];
         if (tt + TPW < kTokPerWave) fetch(t + TPW, zn);          // the next token's logits, a round ahead
-        const bool live = t < T;                                  // uniform inside the group
-        float ss = 0.f;
-#pragma unroll
-        for (int i = 0; i < VPL; i++) ss += z[i] * z[i];
-#pragma unroll
-        for (int o = GS / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-        const float scale = sigma_c / (sqrtf(ss) + eps);
-        if (live) {
-#pragma unroll
-            for (int i = 0; i < VPL; i++) ps[i] += fmaxf(z[i], 0.f) * scale;
-        }
-        unsigned taken = 0;
-        for (int j = 0; j < k; j++) {
-            float bv = -INFINITY;
-            int bi = 0x7fffffff;
-#pragma unroll
-            for (int i = 0; i < VPL; i++) {
-                const int e = sl + GS * i;
-                const bool ok = (e < E) && !((taken >> i) & 1u);
-                if (ok && (z[i] > bv || bi == 0x7fffffff)) { bv = z[i]; bi = e; }
-            }
-#pragma unroll
-            for (int o = GS / 2; o > 0; o >>= 1) {
-                const float ov = __shfl_xor(bv, o, 64);
-                const int oi = __shfl_xor(bi, o, 64);
-                const bool other_valid = oi != 0x7fffffff;
-                const bool mine_valid = bi != 0x7fffffff;
-                const bool take = other_valid && (!mine_valid || ov > bv || (ov == bv && oi < bi));
-                if (take) { bv = ov; bi = oi; }
-            }
-            if (bi % GS == sl) {
-                taken |= 1u << (bi / GS);
-                if (live) {
-                    atomicAdd(&lds_cnt[bi], 1);
-                    topk_idx[(size_t)t * k + j] = bi;
-                    topk_gate[(size_t)t * k + j] = fmaxf(bv, 0.f) * scale;
-                }
-            }
-        }
+        route_select<GS, VPL>(z, sl, E, k, sigma_c, eps, t < T, (size_t)t, topk_idx, topk_gate, lds_cnt, ps);
     }
     // score sums: over the token groups of the wavefront (fixed order), then over the wavefronts
 #pragma unroll
@@ -235,6 +198,13 @@ hipError_t launch_route_score_topk(const unipool_shape& s, const float* logits, 
         route_score_topk_kernel<32, 16><<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps,
                                                                  topk_idx, topk_gate, cnt_part, psum_part);
     route_finalize_kernel<<<s.E, 256, 0, st>>>(cnt_part, psum_part, nblocks, s.E, counts, psum);
+    return hipGetLastError();
+}
+
+hipError_t launch_route_finalize(const unipool_shape& s, const int32_t* cnt_part, const float* psum_part,
+                                 int32_t* counts, float* psum, hipStream_t st) {
+    route_finalize_kernel<<<s.E, 256, 0, st>>>(cnt_part, psum_part, cdiv(s.T, kRouterTokensPerBlock), s.E,
+                                               counts, psum);
     return hipGetLastError();
 }
 
