@@ -267,20 +267,6 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
     }
 }
 
-// Row tiles of one ungrouped matrix (the router's GEMMs): tile i covers rows [i*BM, min(rows, (i+1)*BM)).
-__global__ void build_tiles_flat_kernel(int total_rows, int BM, int32_t* __restrict__ meta) {
-    const int n = (total_rows + BM - 1) / BM;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) meta[0] = n;
-    if (i >= kSchedBase && i < kSchedBase + 4 * kNumXcd) meta[i] = 0;
-    if (i < n) {
-        int32_t* m = meta + kTileBase + 4 * i;
-        m[0] = 0;
-        m[1] = i * BM;
-        m[2] = min(BM, total_rows - i * BM);
-    }
-}
-
 // ---------------------------------------------------------------------------------------------
 // gemm_xw
 // ---------------------------------------------------------------------------------------------
@@ -1183,7 +1169,7 @@ __global__ void reduce_partials_kernel(const float* __restrict__ part, int npart
 // ---------------------------------------------------------------------------------------------
 // launch helpers
 // ---------------------------------------------------------------------------------------------
-constexpr int kFlatBM = 128;
+constexpr int kFlatBM = 128;     // row tiles of ungrouped matrices (router): a token count of 128 per CU fills the chip
 constexpr int kBM = 256, kBN = 256, kBK = 64, kNS = 2;   // gemm_xw: 128-byte row segments per load
 constexpr int kPtqBK = 32, kPtqNS = 4;                      // gemm_ptq
 constexpr int kGemmLds = kNS * kBM * kBK * 2 + (kNS + 1) * kBN * kBK * 2;   // 2 X stages + 3 W stages = 160 KiB
@@ -1234,14 +1220,7 @@ hipError_t run_ptq(const PtqArgs& a, hipStream_t st) {
 }
 
 hipError_t build_tiles(const int32_t* offsets, int E, int total_rows, int32_t* meta, hipStream_t st) {
-    if (offsets == nullptr) {
-        // ungrouped matrices (router): half-height tiles, so that a token count of 128 per CU already
-        // gives every CU a tile
-        const int n = cdiv(total_rows, kFlatBM);
-        build_tiles_flat_kernel<<<cdiv(max(n, 64), 256), 256, 0, st>>>(total_rows, kFlatBM, meta);
-    } else {
-        build_tiles_kernel<<<1, 512, 0, st>>>(offsets, E, total_rows, kBM, meta);
-    }
+    build_tiles_kernel<<<1, 512, 0, st>>>(offsets, E, total_rows, kBM, meta);
     return hipGetLastError();
 }
 

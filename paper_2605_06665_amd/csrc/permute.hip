@@ -4,12 +4,13 @@
 // without order-dependent atomics:
 //   1. hist    : one wavefront per chunk of 64 tokens builds, in LDS, a 64-bit token mask per
 //                expert (atomic OR, order-free) and writes the per-chunk histogram;
-//   2. scan    : exclusive scan of counts -> expert_offsets; per expert, an exclusive scan over
-//                the chunks turns the histograms into per-chunk base rows;
-//   3. scatter : every chunk rebuilds its masks; the rank of a token inside its chunk is the
-//                popcount of the lower lanes' bits; row = chunk base + rank;
-//   4. copy    : one wavefront per token reads the row once and writes its k copies with
-//                16-byte accesses.
+//   2. scan    : one block per expert: its offset (sum of the counts of the experts before it) and
+//                an exclusive scan over the chunks, which turns the histograms into per-chunk
+//                base rows;
+//   3. copy    : one wavefront per token.  The lanes fetch the selections of the token's chunk;
+//                the rank of the token inside its chunk is the number of lower tokens that
+//                selected the same expert (a ballot and a popcount); row = chunk base + rank.
+//                The row is read once and written k times with 16-byte accesses.
 #include "kernels.h"
 
 namespace unipool {
@@ -48,31 +49,36 @@ __global__ __launch_bounds__(256) void permute_hist_kernel(const int32_t* __rest
     for (int e = lane; e < E; e += 64) chunk_hist[(size_t)chunk * E + e] = __popcll(mask[e]);
 }
 
-// expert_offsets = exclusive prefix sum of counts (one block, parallel scan over <= 512 experts).
-__global__ __launch_bounds__(512) void permute_offsets_kernel(const int32_t* __restrict__ counts, int E,
-                                                              int32_t* __restrict__ expert_offsets) {
-    __shared__ int scan[2][512];
-    const int t = threadIdx.x;
-    const int c = t < E ? counts[t] : 0;
-    scan[0][t] = c;
-    __syncthreads();
-    int cur = 0;
-    for (int d = 1; d < 512; d <<= 1) {
-        scan[cur ^ 1][t] = scan[cur][t] + (t >= d ? scan[cur][t - d] : 0);
-        cur ^= 1;
-        __syncthreads();
-    }
-    if (t < E) expert_offsets[t] = scan[cur][t] - c;
-    if (t == 0) expert_offsets[E] = scan[cur][511];
-}
-
-// One block per expert: exclusive scan of its per-chunk histogram, started at the expert's offset.
-__global__ __launch_bounds__(256) void permute_scan_kernel(const int32_t* __restrict__ expert_offsets,
-                                                           int E, int nchunks,
+// One block per expert: its offset = sum of the counts of the experts before it (fixed-shape tree),
+// then the exclusive scan of its per-chunk histogram, started at that offset.
+__global__ __launch_bounds__(256) void permute_scan_kernel(const int32_t* __restrict__ counts, int E,
+                                                           int nchunks, int32_t* __restrict__ expert_offsets,
                                                            int32_t* __restrict__ chunk_hist) {
     __shared__ int scan[2][256];
+    __shared__ int red[256];
     const int e = blockIdx.x, t = threadIdx.x;
-    int carry = expert_offsets[e];
+    int before = 0, all = 0;
+    for (int i = t; i < E; i += 256) {
+        const int c = counts[i];
+        all += c;
+        if (i < e) before += c;
+    }
+    red[t] = before;
+    scan[0][t] = all;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (t < s) {
+            red[t] += red[t + s];
+            scan[0][t] += scan[0][t + s];
+        }
+        __syncthreads();
+    }
+    int carry = red[0];
+    if (t == 0) {
+        expert_offsets[e] = carry;
+        if (e == 0) expert_offsets[E] = scan[0][0];
+    }
+    __syncthreads();
     for (int c0 = 0; c0 < nchunks; c0 += 256) {
         const int c = c0 + t;
         const int h = c < nchunks ? chunk_hist[(size_t)c * E + e] : 0;
@@ -90,41 +96,42 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(const int32_t* __rest
     }
 }
 
-__global__ __launch_bounds__(256) void permute_scatter_kernel(
-    const int32_t* __restrict__ topk_idx, int T, int E, int k,
-    const int32_t* __restrict__ chunk_base, int32_t* __restrict__ row_of_slot,
-    int32_t* __restrict__ slot_of_row) {
-    extern __shared__ unsigned long long lds_mask[];
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int chunk = blockIdx.x * kChunkWaves + wave;
-    const int nchunks = (T + 63) / 64;
-    if (chunk >= nchunks) return;
-    unsigned long long* mask = lds_mask + (size_t)wave * E;
-    int sel[kMaxK];
-    const int t = chunk * 64 + lane;
-    build_masks(mask, topk_idx, t, T, E, k, lane, sel);
-    if (t < T) {
-        const unsigned long long below = (1ull << lane) - 1ull;
-        for (int j = 0; j < k; j++) {
-            const int e = sel[j];
-            const int row = chunk_base[(size_t)chunk * E + e] + __popcll(mask[e] & below);
-            row_of_slot[(size_t)t * k + j] = row;
-            slot_of_row[row] = t * k + j;
-        }
+// Rows of token t (lane-uniform): lane l holds the selections of token chunk*64 + l.
+__device__ __forceinline__ void rows_of_token(const int32_t* __restrict__ topk_idx, int t, int T, int E, int k,
+                                              const int32_t* __restrict__ chunk_base, int lane, int* rows) {
+    const int chunk = t >> 6, tl = t & 63;
+    const int to = chunk * 64 + lane;
+    int other[kMaxK];
+    for (int j = 0; j < k; j++) other[j] = to < T ? topk_idx[(size_t)to * k + j] : -1;
+    const unsigned long long below = (1ull << tl) - 1ull;
+    for (int j = 0; j < k; j++) {
+        const int e = __shfl(other[j], tl, 64);                     // this token's j-th expert
+        bool hit = false;
+        for (int i = 0; i < k; i++) hit |= other[i] == e;
+        const unsigned long long sel = __ballot(hit);               // tokens of the chunk that selected e
+        rows[j] = chunk_base[(size_t)chunk * E + e] + __popcll(sel & below);
     }
 }
 
 // One wavefront per token: 16-byte chunks of the row, read once, written k times.
 __global__ __launch_bounds__(256) void permute_copy_kernel(const uint4* __restrict__ x,
-                                                           const int32_t* __restrict__ row_of_slot,
-                                                           int T, int k, int row_chunks,
-                                                           uint4* __restrict__ x_perm) {
+                                                           const int32_t* __restrict__ topk_idx,
+                                                           const int32_t* __restrict__ chunk_base,
+                                                           int T, int E, int k, int row_chunks,
+                                                           uint4* __restrict__ x_perm,
+                                                           int32_t* __restrict__ row_of_slot,
+                                                           int32_t* __restrict__ slot_of_row) {
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
     int rows[kMaxK];
-    for (int j = 0; j < k; j++) rows[j] = row_of_slot[(size_t)t * k + j];
+    rows_of_token(topk_idx, t, T, E, k, chunk_base, lane, rows);
+    if (lane < k) {
+        int r = rows[0];
+        for (int j = 1; j < k; j++) r = lane == j ? rows[j] : r;
+        row_of_slot[(size_t)t * k + lane] = r;
+        slot_of_row[r] = t * k + lane;
+    }
     const uint4* src = x + (size_t)t * row_chunks;
     for (int c0 = 0; c0 < row_chunks; c0 += 256) {
         uint4 v[4];
@@ -145,14 +152,24 @@ __global__ __launch_bounds__(256) void permute_copy_kernel(const uint4* __restri
 }
 
 // Rows whose byte length is not a multiple of 16 (only possible in float mode with odd d).
-__global__ void permute_copy_scalar_kernel(const uint32_t* __restrict__ x,
-                                           const int32_t* __restrict__ row_of_slot, int T, int k,
-                                           int row_words, uint32_t* __restrict__ x_perm) {
+__global__ __launch_bounds__(64) void permute_copy_scalar_kernel(const uint32_t* __restrict__ x,
+                                                                 const int32_t* __restrict__ topk_idx,
+                                                                 const int32_t* __restrict__ chunk_base,
+                                                                 int T, int E, int k, int row_words,
+                                                                 uint32_t* __restrict__ x_perm,
+                                                                 int32_t* __restrict__ row_of_slot,
+                                                                 int32_t* __restrict__ slot_of_row) {
+    const int lane = threadIdx.x;
     const int t = blockIdx.x;
+    int rows[kMaxK];
+    rows_of_token(topk_idx, t, T, E, k, chunk_base, lane, rows);
     for (int j = 0; j < k; j++) {
-        const int row = row_of_slot[(size_t)t * k + j];
-        for (int c = threadIdx.x; c < row_words; c += blockDim.x)
-            x_perm[(size_t)row * row_words + c] = x[(size_t)t * row_words + c];
+        if (lane == 0) {
+            row_of_slot[(size_t)t * k + j] = rows[j];
+            slot_of_row[rows[j]] = t * k + j;
+        }
+        for (int c = lane; c < row_words; c += 64)
+            x_perm[(size_t)rows[j] * row_words + c] = x[(size_t)t * row_words + c];
     }
 }
 
@@ -166,17 +183,16 @@ hipError_t launch_permute(const unipool_shape& s, const void* x, const int32_t* 
     const int nblocks = cdiv(nchunks, kChunkWaves);
     const size_t lds = (size_t)kChunkWaves * s.E * sizeof(unsigned long long);
     permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_idx, s.T, s.E, s.k, chunk_hist);
-    permute_offsets_kernel<<<1, 512, 0, st>>>(counts, s.E, expert_offsets);
-    permute_scan_kernel<<<s.E, 256, 0, st>>>(expert_offsets, s.E, nchunks, chunk_hist);
-    permute_scatter_kernel<<<nblocks, 256, lds, st>>>(topk_idx, s.T, s.E, s.k, chunk_hist,
-                                                      row_of_slot, slot_of_row);
+    permute_scan_kernel<<<s.E, 256, 0, st>>>(counts, s.E, nchunks, expert_offsets, chunk_hist);
     const size_t row_bytes = (size_t)s.d_model * (s.dtype == UNIPOOL_BF16 ? 2 : 4);
     if (row_bytes % 16 == 0) {
-        permute_copy_kernel<<<cdiv(s.T, 4), 256, 0, st>>>((const uint4*)x, row_of_slot, s.T, s.k,
-                                                          (int)(row_bytes / 16), (uint4*)x_perm);
+        permute_copy_kernel<<<cdiv(s.T, 4), 256, 0, st>>>((const uint4*)x, topk_idx, chunk_hist, s.T, s.E, s.k,
+                                                          (int)(row_bytes / 16), (uint4*)x_perm, row_of_slot,
+                                                          slot_of_row);
     } else {
-        permute_copy_scalar_kernel<<<s.T, 256, 0, st>>>((const uint32_t*)x, row_of_slot, s.T, s.k,
-                                                        (int)(row_bytes / 4), (uint32_t*)x_perm);
+        permute_copy_scalar_kernel<<<s.T, 64, 0, st>>>((const uint32_t*)x, topk_idx, chunk_hist, s.T, s.E, s.k,
+                                                       (int)(row_bytes / 4), (uint32_t*)x_perm, row_of_slot,
+                                                       slot_of_row);
     }
     return hipGetLastError();
 }
