@@ -148,6 +148,8 @@ def main():
         "permute": hbm("permute", act_b * w.T * w.d + act_b * S * w.d + 12 * S, w.L),
         "combine": hbm("combine", act_b * S * w.d + act_b * w.T * w.d + 8 * S, w.L),
         "combine_bwd": hbm("combine_bwd", act_b * w.T * w.d + 2 * act_b * S * w.d + 12 * S, w.L),
+        # x and logits read, dx read and written (the expert path's dx is already there), router gradient written
+        "route_bwd": hbm("route_bwd", 3 * act_b * w.T * w.d + 4 * w.T * w.E + 12 * S + 4 * w.E * w.d, w.L),
     }
     if a.wgrad == "pool" and t_wg_ms > 0:
         wg_tflops = gemm_flops_third * w.L * a.steps / (t_wg_ms * 1e-3) / 1e12

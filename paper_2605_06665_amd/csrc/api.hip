@@ -206,8 +206,6 @@ int unipool_route_bwd(const unipool_shape* shape, const void* x, const void* w_r
                                        (float*)(base + w.dsigma_part), d_sigma, st);
     if (e != hipSuccess) return check_hip(e, "unipool_route_bwd: dz");
     if (mfma_router_supported(*shape) && !force_naive()) {
-        e = launch_fill_zero(base + w.zeros, 256, st);
-        if (e != hipSuccess) return check_hip(e, "unipool_route_bwd: zero page");
         e = mfma_route_bwd_mm(*shape, x, w_router, dz, d_w_router, dx, dx_accumulate,
                               (int32_t*)(base + w.tile_meta), (float*)(base + w.wpart),
                               base + w.zeros, st);

@@ -1152,9 +1152,20 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
     }
 }
 
-__global__ void chunk_offsets_kernel(int T, int chunk_rows, int nchunks, int32_t* __restrict__ off) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i <= nchunks) off[i] = min(T, i * chunk_rows);
+// Set-up of the router weight gradient in one launch: row offsets of the token chunks, the pointer
+// table of the reduction (P, Q, offsets) and the page of zeros that stands in for rows past a chunk.
+__global__ __launch_bounds__(256) void route_bwd_prep_kernel(int T, int chunk_rows, int nchunks,
+                                                             int32_t* __restrict__ off, void** table,
+                                                             const void* p, const void* q,
+                                                             uint32_t* __restrict__ zeros) {
+    const int i = threadIdx.x;
+    for (int c = i; c <= nchunks; c += 256) off[c] = min(T, c * chunk_rows);
+    if (i < 64) zeros[i] = 0u;
+    if (i == 0) {
+        table[0] = const_cast<void*>(p);
+        table[1] = const_cast<void*>(q);
+        table[2] = off;
+    }
 }
 
 __global__ void reduce_partials_kernel(const float* __restrict__ part, int nparts, size_t n,
@@ -1344,14 +1355,17 @@ hipError_t mfma_route_bwd_mm(const unipool_shape& s, const void* x, const void* 
     const int d = s.d_model, E = s.E, T = s.T;
     // d_w_router = dz^T x: the token axis is cut into chunks whose partial products are summed in
     // a fixed order.
-    const int nchunks = min(kRouteBwdSplit, cdiv(T, 256));
+    // as many chunks as give every CU one output tile in a single round
+    const int tiles_per_chunk = cdiv(E, 256) * cdiv(d, 256);
+    const int nchunks = max(1, min(min(kRouteBwdSplit, cdiv(T, 256)), num_cus() / tiles_per_chunk));
     const int chunk_rows = cdiv(cdiv(T, nchunks), 32) * 32;
     const int used = cdiv(T, chunk_rows);
     // the pointer table and the chunk offsets live behind the tile table
     int32_t* off = tile_meta;                       // [used + 1]
     void** tab = reinterpret_cast<void**>(tile_meta + 1024);
-    chunk_offsets_kernel<<<cdiv(used + 1, 256), 256, 0, st>>>(T, chunk_rows, used, off);
-    hipError_t e = launch_set_ptrs(tab, dz, x, off, nullptr, nullptr, st);
+    route_bwd_prep_kernel<<<1, 256, 0, st>>>(T, chunk_rows, used, off, tab, dz, x,
+                                             reinterpret_cast<uint32_t*>(const_cast<void*>(zeros)));
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     PtqArgs a = {};
     a.n_layers = 1;

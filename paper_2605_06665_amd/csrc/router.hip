@@ -8,7 +8,6 @@ namespace unipool {
 
 namespace {
 
-constexpr int kVPL = kMaxE / kWave;       // logits per lane
 constexpr int kWavesPerBlock = 4;
 constexpr int kTokPerWave = kRouterTokensPerBlock / kWavesPerBlock;
 
@@ -100,62 +99,73 @@ __global__ __launch_bounds__(256) void route_finalize_kernel(
     }
 }
 
-template <typename TA>
+// Backward of Eq. 7 per token, a group of GS lanes per token as in the forward selection:
+// ds = aux_coef + dgate on the selected experts; dz = J^T ds with J the Jacobian of
+// s = sigma c relu(z / (||z|| + eps)); d sigma = sum ds * s / sigma.
+template <typename TA, int GS, int VPL>
 __global__ __launch_bounds__(256) void route_bwd_dz_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ topk_idx,
     const float* __restrict__ dgate, const float* __restrict__ aux_coef, int T, int E, int k,
     float sigma, float c, float eps, TA* __restrict__ dz, float* __restrict__ dsigma_part) {
+    constexpr int TPW = 64 / GS;
+    static_assert(kTokPerWave % TPW == 0, "whole rounds per wavefront");
     __shared__ float lds_ds[kWavesPerBlock];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    float coef[kVPL];
+    const int grp = lane / GS, sl = lane % GS;
+    float coef[VPL];
 #pragma unroll
-    for (int i = 0; i < kVPL; i++) {
-        const int e = lane + 64 * i;
+    for (int i = 0; i < VPL; i++) {
+        const int e = sl + GS * i;
         coef[i] = (aux_coef != nullptr && e < E) ? aux_coef[e] : 0.f;
     }
     float dsig = 0.f;
-    const int t0 = blockIdx.x * kRouterTokensPerBlock + wave * kTokPerWave;
-    for (int tt = 0; tt < kTokPerWave; tt++) {
+    const int t0 = blockIdx.x * kRouterTokensPerBlock + wave * kTokPerWave + grp;
+    for (int tt = 0; tt < kTokPerWave; tt += TPW) {
         const int t = t0 + tt;
-        if (t >= T) break;
-        const float* zr = logits + (size_t)t * E;
-        float z[kVPL], ds[kVPL];
+        const bool live = t < T;
+        const int tc = min(t, T - 1);
+        const float* zr = logits + (size_t)tc * E;
+        float z[VPL], ds[VPL];
         float ss = 0.f;
 #pragma unroll
-        for (int i = 0; i < kVPL; i++) {
-            const int e = lane + 64 * i;
+        for (int i = 0; i < VPL; i++) {
+            const int e = sl + GS * i;
             z[i] = (e < E) ? zr[e] : 0.f;
             ss += z[i] * z[i];
             ds[i] = coef[i];
         }
-        ss = wave_sum(ss);
-        for (int j = 0; j < k; j++) {
-            const int sel = topk_idx[(size_t)t * k + j];
-            const float g = dgate[(size_t)t * k + j];
 #pragma unroll
-            for (int i = 0; i < kVPL; i++)
-                if (sel == lane + 64 * i) ds[i] += g;
+        for (int o = GS / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        for (int j = 0; j < k; j++) {
+            const int sel = topk_idx[(size_t)tc * k + j];
+            const float gd = dgate[(size_t)tc * k + j];
+#pragma unroll
+            for (int i = 0; i < VPL; i++)
+                if (sel == sl + GS * i) ds[i] += gd;
         }
         const float n = sqrtf(ss);
         const float inv = 1.0f / (n + eps);
-        float dzh[kVPL];
+        float dzh[VPL];
         float dot = 0.f;
 #pragma unroll
-        for (int i = 0; i < kVPL; i++) {
+        for (int i = 0; i < VPL; i++) {
             const float zh = z[i] * inv;
-            dsig += ds[i] * c * fmaxf(zh, 0.f);
+            if (live) dsig += ds[i] * c * fmaxf(zh, 0.f);
             dzh[i] = (zh > 0.f) ? ds[i] * sigma * c : 0.f;
             dot += dzh[i] * z[i];
         }
-        dot = wave_sum(dot);
-        const float back = (n > 0.f) ? dot * inv * inv / n : 0.f;
 #pragma unroll
-        for (int i = 0; i < kVPL; i++) {
-            const int e = lane + 64 * i;
-            if (e < E) {
-                const float v = (n > 0.f) ? dzh[i] * inv - z[i] * back : 0.f;
-                dz[(size_t)t * E + e] = from_f32<TA>(v);
+        for (int o = GS / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+        const float back = (n > 0.f) ? dot * inv * inv / n : 0.f;
+        if (live) {
+#pragma unroll
+            for (int i = 0; i < VPL; i++) {
+                const int e = sl + GS * i;
+                if (e < E) {
+                    const float v = (n > 0.f) ? dzh[i] * inv - z[i] * back : 0.f;
+                    dz[(size_t)t * E + e] = from_f32<TA>(v);
+                }
             }
         }
     }
@@ -212,14 +222,19 @@ hipError_t launch_route_bwd_dz(const unipool_shape& s, const float* logits, cons
                                const float* dgate, const float* aux_coef, void* dz,
                                float* dsigma_part, float* d_sigma, hipStream_t st) {
     const int nblocks = cdiv(s.T, kRouterTokensPerBlock);
-    if (s.dtype == UNIPOOL_BF16)
-        route_bwd_dz_kernel<bf16><<<nblocks, 256, 0, st>>>(logits, topk_idx, dgate, aux_coef, s.T,
-                                                           s.E, s.k, s.sigma, s.c, s.eps,
-                                                           (bf16*)dz, dsigma_part);
-    else
-        route_bwd_dz_kernel<float><<<nblocks, 256, 0, st>>>(logits, topk_idx, dgate, aux_coef, s.T,
-                                                            s.E, s.k, s.sigma, s.c, s.eps,
-                                                            (float*)dz, dsigma_part);
+#define UNIPOOL_DZ(TA, GS, VPL)                                                                        \
+    route_bwd_dz_kernel<TA, GS, VPL><<<nblocks, 256, 0, st>>>(logits, topk_idx, dgate, aux_coef, s.T, s.E, \
+                                                              s.k, s.sigma, s.c, s.eps, (TA*)dz, dsigma_part)
+    if (s.dtype == UNIPOOL_BF16) {
+        if (s.E <= 128) UNIPOOL_DZ(bf16, 16, 8);
+        else if (s.E <= 256) UNIPOOL_DZ(bf16, 16, 16);
+        else UNIPOOL_DZ(bf16, 32, 16);
+    } else {
+        if (s.E <= 128) UNIPOOL_DZ(float, 16, 8);
+        else if (s.E <= 256) UNIPOOL_DZ(float, 16, 16);
+        else UNIPOOL_DZ(float, 32, 16);
+    }
+#undef UNIPOOL_DZ
     dsigma_finalize_kernel<<<1, 256, 0, st>>>(dsigma_part, nblocks, d_sigma);
     return hipGetLastError();
 }
