@@ -674,6 +674,23 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
         if constexpr (EPI == EPI_SWIGLU_BWD && MTV > 0) {
             if (cols_ok) { UNIPOOL_LOAD_AB(0) }
         }
+        // EPI_STORE adding to the destination: the old values of all strips are requested up front,
+        // in the layout the row segments leave in, so that their latency is paid once per tile.
+        [[maybe_unused]] uint4 oldv[MTV > 0 ? MTV : 1][4];
+        if constexpr (EPI == EPI_STORE) {
+            if (g.add) {
+#pragma unroll
+                for (int tm = 0; tm < MTV; tm++)
+#pragma unroll
+                    for (int it = 0; it < 4; it++) {
+                        const int id = it * 64 + lane;
+                        const int rr = min((wm + 2 * tm) * 32 + id / CPRS, rows - 1);
+                        const int col = min(n0 + wn * 64 + (id % CPRS) * 8, g.N - 8);
+                        oldv[tm][it] = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(g.out0) +
+                                                                       (size_t)(row0 + rr) * g.ldo + col);
+                    }
+            }
+        }
 #pragma unroll
         for (int tm = 0; tm < MTV; tm++) {
             const int strip0 = (wm + 2 * tm) * 32;     // first row of the strip inside the tile
@@ -759,7 +776,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
                         bf16* dst = reinterpret_cast<bf16*>(g.out0) + grow * g.ldo + col;
                         if (g.add) {
                             union { uint4 u; bf16 h[8]; } o, n;
-                            o.u = *reinterpret_cast<const uint4*>(dst);
+                            o.u = oldv[tm][it];
                             n.u = v;
 #pragma unroll
                             for (int i = 0; i < 8; i++) n.h[i] = (bf16)((float)o.h[i] + (float)n.h[i]);
