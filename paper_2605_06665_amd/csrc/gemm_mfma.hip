@@ -992,6 +992,9 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
+#ifdef UNIPOOL_PHASE_TIMES
+    const long long pt_begin = wall_clock64();
+#endif
     const unsigned lds0 = lds_addr_of(smem);
 
     // Per-layer row range and operand pointers of expert e, fetched once into LDS: the K loop then
@@ -1130,6 +1133,9 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
     if (nb > NS - 1) wait_vmcnt<(NS - 1) * LPS>();
     else wait_vmcnt<0>();
     __syncthreads();
+#ifdef UNIPOOL_PHASE_TIMES
+    const long long pt_filled = wall_clock64(), pc_filled = clock64();
+#endif
 #pragma unroll
     for (int j = 0; j < 8; j++) frag_load(0, 0, 0, j);
     {
@@ -1138,35 +1144,62 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
         for (; kb - 1 + NS < nb; kb++) stage_body(std::integral_constant<bool, true>{}, kb);
         for (; kb < nb; kb++) stage_body(std::integral_constant<bool, false>{}, kb);
     }
+#ifdef UNIPOOL_PHASE_TIMES
+    const long long pt_looped = wall_clock64(), pc_looped = clock64();
+#endif
 
     // acc[a][b][r] = out[i = m0 + wm*128 + a*32 + 8*(r/4) + 4*(lane/32) + r%4][j = n0 + wn*128 + b*32 + lane%32]
-    // A wavefront store covers two rows of 32 consecutive floats.  When accumulating, the 16 old
-    // values of a 32x32 block are fetched together before any of them is added and written back.
+    // The 128 x 128 block of a wavefront leaves in four passes of 32 rows through a wave-private LDS
+    // area (rows of 128 floats + 4 of padding), so that every lane stores 16 bytes and a wavefront
+    // instruction covers two whole 512-byte row segments; when accumulating, the old values are
+    // fetched in the same layout.
+    __syncthreads();                          // every wavefront is done with the operand stages
+    {
+        constexpr int SLD = 128 + 4;          // staging row stride in floats
+        float* stg = reinterpret_cast<float*>(smem) + wave * (32 * SLD);
+        const int jw = n0 + wn * 128;         // first column of the wavefront's block
+        const bool vec_ok = (g.ndim & 3) == 0 && (reinterpret_cast<size_t>(g.out) & 15) == 0;
 #pragma unroll
-    for (int a = 0; a < 4; a++) {
+        for (int a = 0; a < 4; a++) {
 #pragma unroll
-        for (int b = 0; b < 4; b++) {
-            const int j = n0 + wn * 128 + b * 32 + (lane & 31);
-            const int i0 = m0 + wm * 128 + a * 32 + 4 * (lane >> 5);
-            float* base = otile + (size_t)i0 * g.ndim + j;
-            float old[16];
-            if (g.accumulate) {
+            for (int b = 0; b < 4; b++)
 #pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const int di = 8 * (r >> 2) + (r & 3);
-                    old[r] = (j < g.ndim && i0 + di < g.mdim) ? base[(size_t)di * g.ndim] : 0.f;
+                for (int r = 0; r < 16; r++)
+                    stg[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * SLD + b * 32 + (lane & 31)] = acc[a][b][r];
+            const int i_blk = m0 + wm * 128 + a * 32;
+#pragma unroll 4
+            for (int it = 0; it < 16; it++) {
+                const int row = it * 2 + (lane >> 5);
+                const int c4 = (lane & 31) * 4;
+                const int i = i_blk + row, j = jw + c4;
+                if (i >= g.mdim || j >= g.ndim) continue;
+                float4 v = *reinterpret_cast<const float4*>(stg + row * SLD + c4);
+                float* dst = otile + (size_t)i * g.ndim + j;
+                if (vec_ok) {                 // then j + 3 < ndim as well
+                    if (g.accumulate) {
+                        const float4 o = *reinterpret_cast<const float4*>(dst);
+                        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                    }
+                    *reinterpret_cast<float4*>(dst) = v;
+                } else {
+                    const float vv[4] = {v.x, v.y, v.z, v.w};
+                    for (int q = 0; q < 4; q++)
+                        if (j + q < g.ndim) dst[q] = (g.accumulate ? dst[q] : 0.f) + vv[q];
                 }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; r++) old[r] = 0.f;
-            }
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const int di = 8 * (r >> 2) + (r & 3);
-                if (j < g.ndim && i0 + di < g.mdim) base[(size_t)di * g.ndim] = old[r] + acc[a][b][r];
             }
         }
     }
+#ifdef UNIPOOL_PHASE_TIMES
+    if (threadIdx.x == 0) {
+        unsigned long long* pt_ = g_phase_times[512 + (blockIdx.x & 255)];
+        atomicAdd(&pt_[0], (unsigned long long)(pt_filled - pt_begin));
+        atomicAdd(&pt_[1], (unsigned long long)(pt_looped - pt_filled));
+        atomicAdd(&pt_[2], (unsigned long long)(wall_clock64() - pt_looped));
+        atomicAdd(&pt_[3], 1ull);
+        atomicAdd(&pt_[6], (unsigned long long)(pc_looped - pc_filled));
+        atomicAdd(&pt_[7], (unsigned long long)nb);
+    }
+#endif
 }
 
 // Set-up of the router weight gradient in one launch: row offsets of the token chunks, the pointer
