@@ -43,7 +43,7 @@ def parse():
                     help="keep one shared pair of A/B buffers and rebuild them before each layer's backward")
     ap.add_argument("--lagged", action="store_true", help="one-step-behind usage statistic across steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--oracle-tokens", type=int, default=1024)
+    ap.add_argument("--oracle-tokens", type=int, default=2048)
     return ap.parse_args()
 
 
