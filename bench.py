@@ -26,10 +26,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # of the 1 GiB copy below), averaged over the four expert-FFN launches of a layer; see
 # profiles/gemm_counters_C5.txt.  Not measured for the other workloads.
 MEASURED_XW_TRAFFIC_BYTES = {"C5": 7.5e9}
-# The same average from the L2's own request counters (TCC_EA0_RDREQ_sum x 128 B, every request of these
-# kernels is a 128-byte one, + WRITE_SIZE): FETCH_SIZE prices a request that is neither 32 bytes nor a
-# "bubble" at 64 bytes, which fits the copy kernel after scaling by 2 but overstates these kernels.
-MEASURED_XW_TRAFFIC_BYTES_RDREQ = {"C5": 6.0e9}
+# The same average from the L2's own request counters (TCC_EA0_RDREQ_sum x 128 B, every read request of these
+# kernels is a 128-byte one, + WRITE_SIZE), same run of bench.py.
+MEASURED_XW_TRAFFIC_BYTES_RDREQ = {"C5": 7.4e9}
 
 
 def parse():
