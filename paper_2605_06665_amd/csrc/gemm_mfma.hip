@@ -118,6 +118,15 @@ __device__ __forceinline__ void glds16(const void* gptr, unsigned lds_addr) {
                  : "memory", "m0");
 }
 
+__device__ __forceinline__ void glds16_s(const void* sbase, unsigned voff, unsigned lds_addr) {
+    // as glds16, the source address given as a wave-uniform base plus a 32-bit byte offset per lane
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(base)
+                 : "memory", "m0");
+}
+
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     // gfx9 encoding: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14; other counters untouched
     static_assert(N >= 0 && N < 64, "vmcnt range");
@@ -967,12 +976,19 @@ struct PtqArgs {
     const void* zeros;           // >= 16 readable zero bytes
 };
 
-template <int BK, int NS>
-__global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
+template <int BK, int NS, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
     constexpr int BM = 256, BN = 256;
+    constexpr int NT = 64 * NW;               // threads
+    constexpr int WNC = NW / 2;               // wavefronts along n (two along m)
+    constexpr int CW = BN / WNC;              // columns of a wavefront's block (128 rows)
+    constexpr int NB = CW / 32;               // its 32-column fragments
+    constexpr int MPS = 4 * NB;               // MFMAs per 16-deep slice
+    constexpr int NF = 4 + NB;                // fragments per slice
+    static_assert(NW == 4 || NW == 8, "2 x 2 or 2 x 4 wavefronts");
     constexpr int PBYTES = BK * BM * 2;
     constexpr int STAGE = 2 * PBYTES;
-    constexpr int PI = BK * BM / 8 / 256;     // loads per wavefront per operand per stage
+    constexpr int PI = BK * BM / 8 / NT;     // loads per wavefront per operand per stage
     constexpr int LPS = 2 * PI;
     constexpr int KS = BK / 16;
     using PT = NTile<BM>;
@@ -990,8 +1006,8 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
     const int n0 = ((lt % per_e) % g.n_tiles) * BN;
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WNC, wn = wave % WNC;
 #ifdef UNIPOOL_PHASE_TIMES
     const long long pt_begin = wall_clock64();
 #endif
@@ -1003,7 +1019,7 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
     __shared__ int lds_r0[kMaxPtqLayers], lds_r1[kMaxPtqLayers];
     __shared__ const bf16* lds_p[kMaxPtqLayers];
     __shared__ const bf16* lds_q[kMaxPtqLayers];
-    for (int l = threadIdx.x; l < g.n_layers; l += 256) {
+    for (int l = threadIdx.x; l < g.n_layers; l += NT) {
         lds_r0[l] = g.off[l][e];
         lds_r1[l] = g.off[l][e + 1];
         lds_p[l] = reinterpret_cast<const bf16*>(g.P[l]);
@@ -1016,7 +1032,7 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
     float* otile = g.out + (long long)e * g.out_stride;
     if (nb == 0) {
         if (!g.accumulate) {
-            for (int i = threadIdx.x; i < BM * BN; i += 256) {
+            for (int i = threadIdx.x; i < BM * BN; i += NT) {
                 const int r = m0 + i / BN, c = n0 + i % BN;
                 if (r < g.mdim && c < g.ndim) otile[(size_t)r * g.ndim + c] = 0.f;
             }
@@ -1025,12 +1041,18 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
     }
 
     // lane geometry of the direct-to-LDS loads: load i of a wavefront fills LDS slots
-    // (i*4 + wave)*64 + lane, i.e. K row 8*i + 2*wave + lane/32, chunk position lane%32.  The
+    // (i*NW + wave)*64 + lane, i.e. K row 2*NW*i + 2*wave + lane/32, chunk position lane%32.  The
     // swizzle depends on (K row & 3) only, which is the same for all i.
     const int krow0 = 2 * wave + (lane >> 5);
     const int cc = (lane & 31) ^ PT::swz(krow0);
     const int pcol = min(m0 + cc * 8, g.mdim - 8);
     const int qcol = min(n0 + cc * 8, g.ndim - 8);
+
+    // A K block that lies inside the row range is loaded from a wave-uniform row address plus these
+    // per-lane byte offsets (no vector arithmetic per load); the last block of a range selects, lane
+    // by lane, between its row and the page of zeros.
+    const unsigned voff_p = ((unsigned)krow0 * (unsigned)g.mdim + (unsigned)pcol) * 2u;
+    const unsigned voff_q = ((unsigned)krow0 * (unsigned)g.ndim + (unsigned)qcol) * 2u;
 
     // load cursor over the rows of expert e, layer after layer
     int ld_layer = -1, ld_r = 0, ld_end = 0;
@@ -1047,59 +1069,84 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
             ld_layer++;
             ld_r = __builtin_amdgcn_readfirstlane(lds_r0[ld_layer]);
             ld_end = __builtin_amdgcn_readfirstlane(lds_r1[ld_layer]);
-            ld_p = uniform_ptr(lds_p[ld_layer]) + pcol;
-            ld_q = uniform_ptr(lds_q[ld_layer]) + qcol;
+            ld_p = uniform_ptr(lds_p[ld_layer]);
+            ld_q = uniform_ptr(lds_q[ld_layer]);
         }
     };
     // load i (0..LPS-1) of the current K block: P rows for i < PI, Q rows after
     auto issue_one = [&](int stage, int i) {
-        const unsigned sb = lds0 + stage * STAGE;
         const int ii = i < PI ? i : i - PI;
-        const int r = ld_r + krow0 + 8 * ii;
-        const void* src = g.zeros;
-        if (r < ld_end)
-            src = i < PI ? (const void*)(ld_p + (size_t)r * g.mdim) : (const void*)(ld_q + (size_t)r * g.ndim);
-        glds16(src, sb + (i < PI ? 0 : PBYTES) + ((ii * 4 + wave) * 64) * 16);
+        const unsigned dst = lds0 + stage * STAGE + (i < PI ? 0 : PBYTES) + ((ii * NW + wave) * 64) * 16;
+        const int rb = ld_r + 2 * NW * ii;                 // wave-uniform
+        if (ld_r + BK <= ld_end) {
+            if (i < PI) glds16_s(ld_p + (size_t)rb * g.mdim, voff_p, dst);
+            else glds16_s(ld_q + (size_t)rb * g.ndim, voff_q, dst);
+        } else {
+            const int r = rb + krow0;
+            const void* src = g.zeros;
+            if (r < ld_end)
+                src = i < PI ? (const void*)(ld_p + (size_t)r * g.mdim + pcol) : (const void*)(ld_q + (size_t)r * g.ndim + qcol);
+            glds16(src, dst);
+        }
     };
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][NB];
 #pragma unroll
     for (int a = 0; a < 4; a++)
 #pragma unroll
-        for (int b = 0; b < 4; b++)
+        for (int b = 0; b < NB; b++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
 
     // software pipeline as in gemm_xw
     static_assert(KS % 2 == 0, "fragment buffers alternate per slice and restart at 0 per stage");
     static_assert(NS >= 2 && (NS - 1) * LPS < 64, "outstanding loads must fit the wait counter");
-    bf16x8 pfr[2][4], qfr[2][4];
-    auto frag_load = [&](int stage, int ks, int buf, int j) {
-        const char* pb = smem + stage * STAGE;
-        if (j < 4) pfr[buf][j] = PT::frag(pb, ks, wm * 128 + j * 32, lane);
-        else qfr[buf][j - 4] = PT::frag(pb + PBYTES, ks, wn * 128 + (j - 4) * 32, lane);
+    bf16x8 pfr[2][4], qfr[2][NB];
+    // fragment u of a slice in the order in which the MFMAs first use them: P0, Q0 .. Q(NB-1), P1, P2, P3
+    // byte offset, within a stage, of the first of the two transposing reads of fragment j at slice 0
+    // (NTile::frag); a slice further down is 16 K rows = 8192 bytes on, the second read 4 K rows = 2048.
+    int foff[NF];
+    {
+        const int krl = 8 * (lane >> 5) + ((lane & 15) >> 2);
+        const int cl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+#pragma unroll
+        for (int j = 0; j < NF; j++)
+            foff[j] = j < 4 ? PT::off(krl, wm * 128 + j * 32 + cl) : PBYTES + PT::off(krl, wn * CW + (j - 4) * 32 + cl);
+    }
+    static_assert(PT::CPR * 16 * 16 == 8192 && PT::CPR * 16 * 4 == 2048, "slice and second-read strides");
+    auto frag_load = [&](int stage, int ks, int buf, int u) {
+        const int j = u == 0 ? 0 : (u <= NB ? 3 + u : u - NB);
+        const char* b = smem + (stage * STAGE + ks * 8192) + foff[j];
+        if (j < 4) pfr[buf][j] = lds_read_tr8(b, b + 2048);
+        else qfr[buf][j - 4] = lds_read_tr8(b, b + 2048);
     };
     auto mfma_one = [&](int buf, int i) {
-        const int a = i >> 2, b = i & 3;
+        const int a = i / NB, b = i % NB;
         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pfr[buf][a], qfr[buf][b], acc[a][b], 0, 0, 0);
     };
+#ifdef UNIPOOL_PHASE_TIMES
+    long long pc_wait = 0, pc_bar = 0;
+#endif
     // ISSUE: the loads of K block kb-1+NS go out during this stage, into the buffer that stage kb-1
-    // has released, one every other MFMA (a burst of loads would stall the wavefronts, MFMAs included,
-    // for as long as the address unit's queue takes to drain).
+    // has released, one every other MFMA of the slices ahead of the last (a burst of loads stalls the
+    // issuing wavefronts, MFMAs included, until the address unit's queue has drained; spreading them
+    // over the last slice as well measured slower).  The wavefronts meet ahead of the last slice:
+    // its MFMAs, whose fragments are in registers, cover the fragment loads of the next stage.
     auto stage_body = [&](auto issue_c, int kb) {
         constexpr bool ISSUE = decltype(issue_c)::value;
         const int stage = kb % NS;
+        constexpr int SL = MPS * (KS - 1);             // MFMA slots that carry the loads
+        static_assert(KS >= 2 && LPS * 2 <= SL, "one load per two MFMA slots");
+        static_assert(MPS >= NF, "the last slice covers the next fragment loads");
         if constexpr (ISSUE) next_block();
-        static_assert(LPS * (KS - 1) * 2 <= 16 * (KS - 1) && KS >= 2, "one load per two MFMA slots");
 #pragma unroll
         for (int ks = 0; ks < KS - 1; ks++) {
 #pragma unroll
-            for (int i = 0; i < 16; i++) {
+            for (int i = 0; i < MPS; i++) {
                 mfma_one(ks & 1, i);
-                if (i < 8) frag_load(stage, ks + 1, (ks + 1) & 1, i);
+                if (i < NF) frag_load(stage, ks + 1, (ks + 1) & 1, i);
                 if constexpr (ISSUE) {
-                    constexpr int SL = 16 * (KS - 1);
-                    const int slot = ks * 16 + i;
+                    const int slot = ks * MPS + i;
 #pragma unroll
                     for (int u = 0; u < LPS; u++)
                         if (u * SL / LPS == slot) issue_one((kb + NS - 1) % NS, u);
@@ -1109,16 +1156,23 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
         }
         if constexpr (ISSUE) ld_r += BK;
         constexpr int buf = (KS - 1) & 1;
-#pragma unroll
-        for (int i = 0; i < 4; i++) mfma_one(buf, i);
-        __builtin_amdgcn_sched_barrier(0);
+#ifdef UNIPOOL_PHASE_TIMES
+        const long long pw0 = clock64();
+#endif
         if (nb - 2 - kb >= NS - 2) wait_vmcnt<(NS - 2) * LPS>();
         else wait_vmcnt<0>();
+#ifdef UNIPOOL_PHASE_TIMES
+        const long long pw1 = clock64();
+#endif
         __syncthreads();
+#ifdef UNIPOOL_PHASE_TIMES
+        pc_wait += pw1 - pw0;
+        pc_bar += clock64() - pw1;
+#endif
 #pragma unroll
-        for (int i = 0; i < 12; i++) {
-            mfma_one(buf, 4 + i);
-            if (i < 8) frag_load((kb + 1) % NS, 0, 0, i);
+        for (int i = 0; i < MPS; i++) {
+            mfma_one(buf, i);
+            if (i < NF) frag_load((kb + 1) % NS, 0, 0, i);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -1137,7 +1191,7 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
     const long long pt_filled = wall_clock64(), pc_filled = clock64();
 #endif
 #pragma unroll
-    for (int j = 0; j < 8; j++) frag_load(0, 0, 0, j);
+    for (int j = 0; j < NF; j++) frag_load(0, 0, 0, j);
     {
         stage_body(std::integral_constant<bool, false>{}, 0);       // nb >= 1 here
         int kb = 1;
@@ -1148,29 +1202,31 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
     const long long pt_looped = wall_clock64(), pc_looped = clock64();
 #endif
 
-    // acc[a][b][r] = out[i = m0 + wm*128 + a*32 + 8*(r/4) + 4*(lane/32) + r%4][j = n0 + wn*128 + b*32 + lane%32]
-    // The 128 x 128 block of a wavefront leaves in four passes of 32 rows through a wave-private LDS
-    // area (rows of 128 floats + 4 of padding), so that every lane stores 16 bytes and a wavefront
-    // instruction covers two whole 512-byte row segments; when accumulating, the old values are
+    // acc[a][b][r] = out[i = m0 + wm*128 + a*32 + 8*(r/4) + 4*(lane/32) + r%4][j = n0 + wn*CW + b*32 + lane%32]
+    // The 128 x CW block of a wavefront leaves in four passes of 32 rows through a wave-private LDS
+    // area (rows of CW floats + 4 of padding), so that every lane stores 16 bytes and a wavefront
+    // instruction covers whole row segments of 4*CW bytes; when accumulating, the old values are
     // fetched in the same layout.
     __syncthreads();                          // every wavefront is done with the operand stages
     {
-        constexpr int SLD = 128 + 4;          // staging row stride in floats
+        constexpr int SLD = CW + 4;           // staging row stride in floats
+        constexpr int LPR = CW / 4;           // lanes per row
+        constexpr int RPI = 64 / LPR;         // rows per wavefront instruction
         float* stg = reinterpret_cast<float*>(smem) + wave * (32 * SLD);
-        const int jw = n0 + wn * 128;         // first column of the wavefront's block
+        const int jw = n0 + wn * CW;          // first column of the wavefront's block
         const bool vec_ok = (g.ndim & 3) == 0 && (reinterpret_cast<size_t>(g.out) & 15) == 0;
 #pragma unroll
         for (int a = 0; a < 4; a++) {
 #pragma unroll
-            for (int b = 0; b < 4; b++)
+            for (int b = 0; b < NB; b++)
 #pragma unroll
                 for (int r = 0; r < 16; r++)
                     stg[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * SLD + b * 32 + (lane & 31)] = acc[a][b][r];
             const int i_blk = m0 + wm * 128 + a * 32;
 #pragma unroll 4
-            for (int it = 0; it < 16; it++) {
-                const int row = it * 2 + (lane >> 5);
-                const int c4 = (lane & 31) * 4;
+            for (int it = 0; it < 32 / RPI; it++) {
+                const int row = it * RPI + lane / LPR;
+                const int c4 = (lane % LPR) * 4;
                 const int i = i_blk + row, j = jw + c4;
                 if (i >= g.mdim || j >= g.ndim) continue;
                 float4 v = *reinterpret_cast<const float4*>(stg + row * SLD + c4);
@@ -1196,6 +1252,8 @@ __global__ __launch_bounds__(256) void gemm_ptq_kernel(const PtqArgs g) {
         atomicAdd(&pt_[1], (unsigned long long)(pt_looped - pt_filled));
         atomicAdd(&pt_[2], (unsigned long long)(wall_clock64() - pt_looped));
         atomicAdd(&pt_[3], 1ull);
+        atomicAdd(&pt_[4], (unsigned long long)pc_wait);
+        atomicAdd(&pt_[5], (unsigned long long)pc_bar);
         atomicAdd(&pt_[6], (unsigned long long)(pc_looped - pc_filled));
         atomicAdd(&pt_[7], (unsigned long long)nb);
     }
@@ -1232,7 +1290,7 @@ __global__ void reduce_partials_kernel(const float* __restrict__ part, int npart
 // ---------------------------------------------------------------------------------------------
 constexpr int kFlatBM = 128;     // row tiles of ungrouped matrices (router): a token count of 128 per CU fills the chip
 constexpr int kBM = 256, kBN = 256, kBK = 64, kNS = 2;   // gemm_xw: 128-byte row segments per load
-constexpr int kPtqBK = 32, kPtqNS = 4;                      // gemm_ptq
+constexpr int kPtqBK = 32, kPtqNS = 4, kPtqWaves = 8;       // gemm_ptq
 constexpr int kGemmLds = kNS * kBM * kBK * 2 + (kNS + 1) * kBN * kBK * 2;   // 2 X stages + 3 W stages = 160 KiB
 constexpr int kPtqLds = kPtqNS * 2 * kPtqBK * 256 * 2;            // 128 KiB
 
@@ -1266,7 +1324,7 @@ hipError_t run_xw(GemmArgs a, int max_row_tiles, hipStream_t st) {
 }
 
 hipError_t run_ptq(const PtqArgs& a, hipStream_t st) {
-    auto kern = gemm_ptq_kernel<kPtqBK, kPtqNS>;
+    auto kern = gemm_ptq_kernel<kPtqBK, kPtqNS, kPtqWaves>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1276,7 +1334,7 @@ hipError_t run_ptq(const PtqArgs& a, hipStream_t st) {
     }
     const int total = a.E * a.m_tiles * a.n_tiles;
     const int grid = cdiv(total, kNumXcd) * kNumXcd;
-    kern<<<grid, 256, kPtqLds, st>>>(a);
+    kern<<<grid, 64 * kPtqWaves, kPtqLds, st>>>(a);
     return hipGetLastError();
 }
 
