@@ -184,6 +184,23 @@ template <int BC> struct NTile {
     }
 };
 
+// N-contiguous tile read for v_mfma_f32_16x16x32_bf16: a fragment is 16 columns x 32 reduction
+// indices; lane l ends with column l%16 and indices 8*(l/16) .. +7.  Two transposing reads (K rows
+// krow and krow+4) of the 4 x 16 block that a group of 16 lanes addresses.  The swizzle keeps the four
+// K rows of a group and the groups 8 rows apart in different banks.
+template <int BC> struct NTile16 {
+    static constexpr int CPR = BC / 8;
+    __device__ static __forceinline__ int swz(int krow) { return ((krow & 3) << 2) | (((krow >> 3) & 1) << 1); }
+    __device__ static __forceinline__ int off(int krow, int col) {
+        return (krow * CPR + ((col >> 3) ^ swz(krow))) * 16 + (col & 7) * 2;
+    }
+    // byte offset of the first read of the fragment at columns col0 .. col0+15, reduction indices 0..31;
+    // the second read is 4 K rows (4 * CPR * 16 bytes) further on
+    __device__ static __forceinline__ int frag_off(int col0, int lane) {
+        return off(8 * (lane >> 4) + ((lane & 15) >> 2), col0 + 4 * (lane & 3));
+    }
+};
+
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
     union { bf16 h[4]; uint2 u; } p;
     p.h[0] = (bf16)a;
@@ -284,6 +301,8 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
 // group sit on the same SIMD, so a SIMD always carries the same share of the tile, however many
 // strips hold rows.  MTV = strips of THIS wavefront that hold rows (0..4); the body is instantiated
 // per MTV so that the K loop is straight-line code and absent strips have no accumulators.
+// The products are v_mfma_f32_16x16x32_bf16 (at the card's power limit this form sustains about a
+// sixth more than 32x32x16): a strip is two 16-row halves, the 64 columns four 16-column blocks.
 constexpr int kXwWaves = 8;
 constexpr int kXwThreads = kXwWaves * 64;
 
@@ -315,12 +334,12 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     constexpr int WBYTES = BN * BK * 2;
     constexpr int XI = BM * BK / 8 / (NW * 64);   // direct-to-LDS loads per wavefront, X tile
     constexpr int WI = BN * BK / 8 / (NW * 64);
-    constexpr int KS = BK / 16;
-    static_assert(KS % 2 == 0, "fragment buffers alternate per slice and restart at 0 per stage");
+    constexpr int KS = BK / 32;                   // slices of 32 reduction indices per stage
+    static_assert(KS == 2, "the stage body below is written for two slices");
     static_assert(BM == 256 && BN == 256 && NW == 8, "2 x 4 wavefronts, strips interleaved by 2");
     using XT = KTile<BK>;
     using WTK = KTile<BK>;
-    using WTN = NTile<BN>;
+    using WTN = NTile16<BN>;
 
     // The per-MTV bodies are alternatives of one switch.  Their set-up code is identical, and if
     // the compiler merges it in front of the switch the merged values stay live across all the
@@ -394,13 +413,14 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     };
     set_sources(expert, row0, rows, nt);
 
-    f32x16 acc[MTV > 0 ? MTV : 1][TN];
+    // acc[tm][mh][nb]: strip tm of this wavefront, 16-row half mh, 16-column block nb
+    f32x4 acc[MTV > 0 ? MTV : 1][2][4];
 #pragma unroll
     for (int tm = 0; tm < MTV; tm++)
 #pragma unroll
-        for (int tn = 0; tn < TN; tn++)
+        for (int mh = 0; mh < 2; mh++)
 #pragma unroll
-            for (int r = 0; r < 16; r++) acc[tm][tn][r] = 0.f;
+            for (int nb = 0; nb < 4; nb++) acc[tm][mh][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // LDS rows (K-contiguous W) or columns (N-contiguous W) of this wavefront's two fragments
     int wpos[TN];
@@ -433,25 +453,41 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     const int x0 = g0 & 1, w0 = g0 % 3;
     auto xbuf = [&](int kt) { return (kt + x0) & 1; };
     auto wbuf = [&](int kt) { return (kt + w0) % 3; };
-    bf16x8 wfr[2][TN], xfr[2][MTV > 0 ? MTV : 1];
-    constexpr int NM = MTV * TN;                    // MFMAs per slice
-    constexpr int NL = MTV > 0 ? MTV + TN : 0;      // fragments per slice
-    auto frag_load = [&](int kt, int ks, int buf, int j) {
-        if (j < TN) {
-            const char* wb = smem + WBASE + wbuf(kt) * WBYTES;
-            if constexpr (WK)
-                wfr[buf][j] = lds_read16(wb + WTK::off(wpos[j] + (lane & 31), ks * 2 + (lane >> 5)));
-            else
-                wfr[buf][j] = WTN::frag(wb, ks, wpos[j], lane);
+    // Fragments of one slice: W block nb (16 columns x 32 indices, the MFMA A operand) and X fragment
+    // a = mh * MTV + tm (16 rows x 32 indices, the B operand), one register set each.  A slice is two
+    // halves of 4 * MTV MFMA slots; slot nb * MTV + tm of the first half takes the upper rows of the
+    // strips (mh = 0), of the second half the lower rows, so X[0 .. MTV) and W[0..2] are free for the
+    // next slice's data during the second half, W[3] and X[MTV .. 2 MTV) at its end.
+    constexpr int NXF = 2 * MTV;
+    constexpr int HM = 4 * MTV;
+    bf16x8 wfr[4], xfr[NXF > 0 ? NXF : 1];
+    // per-lane part of the fragment addresses (rows that are multiples of 16 further down add whole rows)
+    const int l16 = lane & 15, lg = lane >> 4;
+    const int koff0 = XT::off(l16, lg), koff1 = XT::off(l16, 4 + lg);       // K-contiguous tiles, slice 0 / 1
+    static_assert(XT::CPR == 8, "a slice is four 16-byte chunks of a 128-byte row");
+    [[maybe_unused]] int noff[4];                                         // N-contiguous W
+    if constexpr (!WK) {
+#pragma unroll
+        for (int nb = 0; nb < 4; nb++) noff[nb] = WTN::frag_off(wpos[nb >> 1] + 16 * (nb & 1), lane);
+    }
+    constexpr int ROWB = BK * 2;                                           // bytes per K-contiguous row
+    auto load_w = [&](int kt, int ks, int nb) {
+        const char* wb = smem + WBASE + wbuf(kt) * WBYTES;
+        if constexpr (WK) {
+            wfr[nb] = lds_read16(wb + (wpos[nb >> 1] + 16 * (nb & 1)) * ROWB + (ks ? koff1 : koff0));
         } else {
-            const char* xb = smem + xbuf(kt) * XBYTES;
-            const int strip = wm + 2 * (j - TN);
-            xfr[buf][j - TN] = lds_read16(xb + XT::off(strip * 32 + (lane & 31), ks * 2 + (lane >> 5)));
+            const char* p = wb + ks * (32 * WTN::CPR * 16) + noff[nb];
+            wfr[nb] = lds_read_tr8(p, p + 4 * WTN::CPR * 16);
         }
     };
-    auto mfma_one = [&](int buf, int i) {
-        const int tm = i / TN, tn = i % TN;
-        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[buf][tn], xfr[buf][tm], acc[tm][tn], 0, 0, 0);
+    auto load_x = [&](int kt, int ks, int a) {
+        const int tm = a % (MTV > 0 ? MTV : 1), mh = a / (MTV > 0 ? MTV : 1);
+        const char* xb = smem + xbuf(kt) * XBYTES;
+        xfr[a] = lds_read16(xb + ((wm + 2 * tm) * 32 + 16 * mh) * ROWB + (ks ? koff1 : koff0));
+    };
+    auto mfma_one = [&](int a, int nb) {
+        const int tm = a % (MTV > 0 ? MTV : 1), mh = a / (MTV > 0 ? MTV : 1);
+        acc[tm][mh][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfr[nb], xfr[a], acc[tm][mh][nb], 0, 0, 0);
     };
     // KTAIL: K is not a multiple of BK; chunks past K come from a page of zeros in both operands
     static_assert(!KTAIL || !WK, "the reduction tail is implemented for N-contiguous W only");
@@ -480,15 +516,30 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
         glds16(src, lds0 + WBASE + wbuf(kb) * WBYTES + ((i * NW + wave) * 64) * 16);
     };
     // One stage.  IX / IW: the loads of X(kt+1) / W(kt+2) go out during this stage, into the buffers
-    // that stage kt-1 has released.  They are spread over the slices before the meeting point, X in
+    // that stage kt-1 has released.  They are spread over the MFMA slots before the meeting point, X in
     // the first half (it has to land within this stage) and W in the second: a wavefront whose load
     // finds the address unit's queue full stands still, MFMAs included, so a burst of loads from all
-    // wavefronts at once would cost the matrix cores the whole time the queue takes to drain.
+    // wavefronts at once would cost the matrix cores the whole time the queue takes to drain.  The
+    // wavefronts meet between the halves of the second slice: stage kt+1 has landed, nobody reads
+    // stage kt any more, and the second half, whose operands are in registers, covers the first
+    // fragment loads of stage kt+1.
     auto stage_body = [&](auto ix_c, auto iw_c, int kt) {
         constexpr bool IX = decltype(ix_c)::value;
         constexpr bool IW = decltype(iw_c)::value;
-        constexpr int SPS = NM > NL ? NM : NL;        // slots per slice
-        constexpr int SL = (KS - 1) * SPS;            // slots before the last slice
+        constexpr int SL = 3 * HM;                    // slots before the meeting point
+        constexpr int H = SL / 2;
+        auto slot_loads = [&](int slot) {
+            if constexpr (IX) {
+#pragma unroll
+                for (int u = 0; u < XI; u++)
+                    if (u * H / XI == slot) issue_x(kt + 1, u, kt + 1);
+            }
+            if constexpr (IW) {
+#pragma unroll
+                for (int u = 0; u < WI; u++)
+                    if (H + u * (SL - H) / WI == slot) issue_w(kt + 2, u, kt + 2);
+            }
+        };
         if constexpr (SL == 0) {
             if constexpr (IX) {
 #pragma unroll
@@ -499,33 +550,29 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
                 for (int u = 0; u < WI; u++) issue_w(kt + 2, u, kt + 2);
             }
         }
+        auto first_half = [&](int ks, int slot0) {
 #pragma unroll
-        for (int ks = 0; ks < KS - 1; ks++) {
-#pragma unroll
-            for (int i = 0; i < SPS; i++) {
-                if (i < NM) mfma_one(ks & 1, i);
-                if (i < NL) frag_load(kt, ks + 1, (ks + 1) & 1, i);
-                constexpr int H = SL / 2;
-                const int slot = ks * SPS + i;
-                if constexpr (IX) {
-#pragma unroll
-                    for (int u = 0; u < XI; u++)
-                        if (u * H / XI == slot) issue_x(kt + 1, u, kt + 1);
-                }
-                if constexpr (IW) {
-#pragma unroll
-                    for (int u = 0; u < WI; u++)
-                        if (H + u * (SL - H) / WI == slot) issue_w(kt + 2, u, kt + 2);
-                }
+            for (int sl = 0; sl < HM; sl++) {
+                mfma_one(sl % MTV, sl / MTV);
+                if (sl == 0) load_w(kt, ks, 3);                        // what the previous slice still held
+                if (sl >= 1 && sl <= MTV) load_x(kt, ks, MTV + sl - 1);
+                slot_loads(slot0 + sl);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        }
-        // last slice: a quarter of its MFMAs covers the meeting of the wavefronts
-        constexpr int buf = (KS - 1) & 1;
-        constexpr int Q = NM / 4;
+        };
+        auto second_half = [&](int nkt, int nks, int slot0) {       // (nkt, nks): the slice that follows
 #pragma unroll
-        for (int i = 0; i < Q; i++) mfma_one(buf, i);
-        __builtin_amdgcn_sched_barrier(0);
+            for (int sl = 0; sl < HM; sl++) {
+                mfma_one(MTV + sl % MTV, sl / MTV);
+                if (sl < MTV) load_x(nkt, nks, sl);
+                else if (sl % MTV == 0) load_w(nkt, nks, sl / MTV - 1);
+                if (slot0 >= 0) slot_loads(slot0 + sl);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        first_half(0, 0);
+        second_half(kt, 1, HM);
+        first_half(1, 2 * HM);
         // X(kt+1) and W(kt+1) must have landed.  Loads complete in issue order and every stage
         // issues X first, so only the W loads of stage kt+2 may remain (NSX = 2: no younger X batch).
 #ifdef UNIPOOL_PHASE_TIMES
@@ -542,13 +589,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
         acc_wait_ += c1_ - c0_;
         acc_bar_ += c2_ - c1_;
 #endif
-        constexpr int REST = NM - Q;
-#pragma unroll
-        for (int i = 0; i < (REST > NL ? REST : NL); i++) {
-            if (i < REST) mfma_one(buf, Q + i);
-            if (i < NL) frag_load(kt + 1, 0, 0, i);     // after the last stage: unused, in bounds
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        second_half(kt + 1, 0, -1);                   // after the last stage: unused, in bounds
     };
     // prologue: X(0) W(0) X(1) W(1) W(2), less what the previous tile has requested already
     if (!(pre & 1)) {
@@ -579,7 +620,11 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     PHASE_CLOCK(cl0_);
 #endif
 #pragma unroll
-    for (int j = 0; j < NL; j++) frag_load(0, 0, 0, j);
+    for (int a = 0; a < MTV; a++) load_x(0, 0, a);
+    if constexpr (MTV > 0) {
+#pragma unroll
+        for (int nb = 0; nb < 3; nb++) load_w(0, 0, nb);
+    }
     {
         using T = std::integral_constant<bool, true>;
         using F = std::integral_constant<bool, false>;
@@ -614,44 +659,43 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
 #endif
 
     // ---- epilogue ---------------------------------------------------------------------------------
-    // acc[tm][tn][r] = C[row (wm + 2 tm)*32 + lane%32][col wpos-relative 8*(r/4) + 4*(lane/32) + r%4]
-    const int lrow = lane & 31;
-    const int lhalf = lane >> 5;
+    // acc[tm][mh][nb][r] = C[row (wm + 2 tm)*32 + 16 mh + lane%16][column 16 nb + 4*(lane/16) + r of the wavefront's 64]
 
     if constexpr (EPI == EPI_ROUTE) {
         // the logits of the tile go to LDS in float; the selection follows once all wavefronts are done
         float* tile = reinterpret_cast<float*>(smem);
 #pragma unroll
-        for (int tm = 0; tm < MTV; tm++) {
-            const int r_in = (wm + 2 * tm) * 32 + lrow;
-            if (r_in < kRouteRows) {
+        for (int tm = 0; tm < MTV; tm++)
 #pragma unroll
-                for (int tn = 0; tn < TN; tn++)
+            for (int mh = 0; mh < 2; mh++) {
+                const int r_in = (wm + 2 * tm) * 32 + 16 * mh + l16;
+                if (r_in < kRouteRows) {
 #pragma unroll
-                    for (int q = 0; q < 4; q++) {
-                        const int col = wpos[tn] + 8 * q + 4 * lhalf;
+                    for (int nb = 0; nb < 4; nb++) {
+                        const int col = wpos[nb >> 1] + 16 * (nb & 1) + 4 * lg;
                         *reinterpret_cast<float4*>(tile + r_in * kRouteLdz + col) =
-                            make_float4(acc[tm][tn][4 * q], acc[tm][tn][4 * q + 1], acc[tm][tn][4 * q + 2],
-                                        acc[tm][tn][4 * q + 3]);
+                            make_float4(acc[tm][mh][nb][0], acc[tm][mh][nb][1], acc[tm][mh][nb][2], acc[tm][mh][nb][3]);
                     }
+                }
             }
-        }
     } else if constexpr (EPI == EPI_F32) {
         float* out = reinterpret_cast<float*>(g.out0);
 #pragma unroll
-        for (int tm = 0; tm < MTV; tm++) {
-            const int r_in = (wm + 2 * tm) * 32 + lrow;
-            if (r_in < rows) {
-                float* orow = out + (size_t)(row0 + r_in) * g.ldo;
+        for (int tm = 0; tm < MTV; tm++)
 #pragma unroll
-                for (int tn = 0; tn < TN; tn++)
+            for (int mh = 0; mh < 2; mh++) {
+                const int r_in = (wm + 2 * tm) * 32 + 16 * mh + l16;
+                if (r_in < rows) {
+                    float* orow = out + (size_t)(row0 + r_in) * g.ldo;
 #pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        const int col = n0 + wpos[tn] + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-                        if (col < g.N) orow[col] = acc[tm][tn][r];
-                    }
+                    for (int nb = 0; nb < 4; nb++)
+#pragma unroll
+                        for (int r = 0; r < 4; r++) {
+                            const int col = n0 + wpos[nb >> 1] + 16 * (nb & 1) + 4 * lg + r;
+                            if (col < g.N) orow[col] = acc[tm][mh][nb][r];
+                        }
+                }
             }
-        }
     } else {
         using SG = Staging<EPI>;
         constexpr int SROW = SG::SROW;                  // staging row stride in bytes
@@ -706,28 +750,29 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
             // -- registers -> staging rows
             if constexpr (EPI == EPI_STORE) {
 #pragma unroll
-                for (int tn = 0; tn < TN; tn++)
+                for (int mh = 0; mh < 2; mh++)
 #pragma unroll
-                    for (int q = 0; q < 4; q++) {
-                        const int c = tn * 32 + 8 * q + 4 * lhalf;
-                        *reinterpret_cast<uint2*>(stg + lrow * SROW + c * 2) =
-                            pack4(acc[tm][tn][4 * q], acc[tm][tn][4 * q + 1], acc[tm][tn][4 * q + 2],
-                                  acc[tm][tn][4 * q + 3]);
+                    for (int nb = 0; nb < 4; nb++) {
+                        const int c = 16 * nb + 4 * lg;
+                        *reinterpret_cast<uint2*>(stg + (16 * mh + l16) * SROW + c * 2) =
+                            pack4(acc[tm][mh][nb][0], acc[tm][mh][nb][1], acc[tm][mh][nb][2], acc[tm][mh][nb][3]);
                     }
             } else if constexpr (EPI == EPI_SWIGLU_FWD) {
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
-                    const int c = 8 * q + 4 * lhalf;
+                    const int mh = q >> 1, nbg = q & 1;       // blocks nbg and 2 + nbg: gate and up of the same columns
+                    const int c = 16 * nbg + 4 * lg;
+                    char* srow = stg + (16 * mh + l16) * SROW;
                     float a[4], b[4], h[4];
 #pragma unroll
                     for (int i = 0; i < 4; i++) {
-                        a[i] = acc[tm][0][4 * q + i];
-                        b[i] = acc[tm][1][4 * q + i];
+                        a[i] = acc[tm][mh][nbg][i];
+                        b[i] = acc[tm][mh][2 + nbg][i];
                         h[i] = silu_f(a[i]) * b[i];
                     }
-                    *reinterpret_cast<uint2*>(stg + lrow * SROW + c * 2) = pack4(a[0], a[1], a[2], a[3]);
-                    *reinterpret_cast<uint2*>(stg + lrow * SROW + (32 + c) * 2) = pack4(b[0], b[1], b[2], b[3]);
-                    *reinterpret_cast<uint2*>(stg + lrow * SROW + (64 + c) * 2) = pack4(h[0], h[1], h[2], h[3]);
+                    *reinterpret_cast<uint2*>(srow + c * 2) = pack4(a[0], a[1], a[2], a[3]);
+                    *reinterpret_cast<uint2*>(srow + (32 + c) * 2) = pack4(b[0], b[1], b[2], b[3]);
+                    *reinterpret_cast<uint2*>(srow + (64 + c) * 2) = pack4(h[0], h[1], h[2], h[3]);
                 }
             } else {   // EPI_SWIGLU_BWD
                 if (cols_ok) {
@@ -743,14 +788,14 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
                     if (tm + 1 < MTV) { UNIPOOL_LOAD_AB(tm + 1) }
                 }
 #pragma unroll
-                for (int tn = 0; tn < TN; tn++)
+                for (int mh = 0; mh < 2; mh++)
 #pragma unroll
-                    for (int q = 0; q < 4; q++) {
-                        const int c = tn * 32 + 8 * q + 4 * lhalf;     // column inside the wave's 64
+                    for (int nb = 0; nb < 4; nb++) {
+                        const int c = 16 * nb + 4 * lg;                 // column inside the wave's 64
                         float da[4] = {0.f, 0.f, 0.f, 0.f}, db[4] = {0.f, 0.f, 0.f, 0.f};
                         // a lane overwrites exactly the eight bytes of A and of B it has read
-                        uint2* pa = reinterpret_cast<uint2*>(stg + lrow * SROW + c * 2);
-                        uint2* pb = reinterpret_cast<uint2*>(stgb + lrow * SROW + c * 2);
+                        uint2* pa = reinterpret_cast<uint2*>(stg + (16 * mh + l16) * SROW + c * 2);
+                        uint2* pb = reinterpret_cast<uint2*>(stgb + (16 * mh + l16) * SROW + c * 2);
                         if (cols_ok) {
                             union { uint2 u; bf16 h[4]; } a4, b4;
                             a4.u = *pa;
@@ -758,7 +803,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
 #pragma unroll
                             for (int i = 0; i < 4; i++) {
                                 const float a = (float)a4.h[i], b = (float)b4.h[i];
-                                const float dh = acc[tm][tn][4 * q + i];
+                                const float dh = acc[tm][mh][nb][i];
                                 const float sg = logistic_f(a);
                                 da[i] = dh * b * sg * (1.0f + a * (1.0f - sg));
                                 db[i] = dh * a * sg;
@@ -978,20 +1023,19 @@ struct PtqArgs {
 
 template <int BK, int NS, int NW>
 __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
+    // 256 x 256 float tile, 2 x 4 wavefronts of 128 x 64, v_mfma_f32_16x16x32_bf16 (at the card's power
+    // limit it sustains about a sixth more than the 32x32x16 form): 8 x 4 accumulator blocks of 16 x 16.
     constexpr int BM = 256, BN = 256;
     constexpr int NT = 64 * NW;               // threads
     constexpr int WNC = NW / 2;               // wavefronts along n (two along m)
     constexpr int CW = BN / WNC;              // columns of a wavefront's block (128 rows)
-    constexpr int NB = CW / 32;               // its 32-column fragments
-    constexpr int MPS = 4 * NB;               // MFMAs per 16-deep slice
-    constexpr int NF = 4 + NB;                // fragments per slice
-    static_assert(NW == 4 || NW == 8, "2 x 2 or 2 x 4 wavefronts");
+    constexpr int NA = 8, NB = CW / 16;       // 16-wide fragments of P and of Q per wavefront
+    static_assert(NW == 8 && BK == 32 && NB == 4, "one 32-deep slice per stage, 8 x 4 blocks per wavefront");
     constexpr int PBYTES = BK * BM * 2;
     constexpr int STAGE = 2 * PBYTES;
-    constexpr int PI = BK * BM / 8 / NT;     // loads per wavefront per operand per stage
+    constexpr int PI = BK * BM / 8 / NT;      // loads per wavefront per operand per stage
     constexpr int LPS = 2 * PI;
-    constexpr int KS = BK / 16;
-    using PT = NTile<BM>;
+    using PT = NTile16<BM>;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int per_e = g.m_tiles * g.n_tiles;
@@ -1042,7 +1086,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
 
     // lane geometry of the direct-to-LDS loads: load i of a wavefront fills LDS slots
     // (i*NW + wave)*64 + lane, i.e. K row 2*NW*i + 2*wave + lane/32, chunk position lane%32.  The
-    // swizzle depends on (K row & 3) only, which is the same for all i.
+    // swizzle depends on bits 0, 1 and 3 of the K row, which are the same for all i.
+    static_assert((2 * NW) % 16 == 0, "the K rows of a lane's loads differ by multiples of 16");
     const int krow0 = 2 * wave + (lane >> 5);
     const int cc = (lane & 31) ^ PT::swz(krow0);
     const int pcol = min(m0 + cc * 8, g.mdim - 8);
@@ -1090,72 +1135,58 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
         }
     };
 
-    f32x16 acc[4][NB];
+    f32x4 acc[NA][NB];
 #pragma unroll
-    for (int a = 0; a < 4; a++)
+    for (int a = 0; a < NA; a++)
 #pragma unroll
-        for (int b = 0; b < NB; b++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[a][b][r] = 0.f;
+        for (int b = 0; b < NB; b++) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // software pipeline as in gemm_xw
-    static_assert(KS % 2 == 0, "fragment buffers alternate per slice and restart at 0 per stage");
+    // Fragments: P block a (rows of the output) and Q block b (columns), one register set each.  A
+    // stage is 32 MFMA slots, slot 4b + a in each half (a = 0..3 in the first half, 4..7 in the
+    // second), so P[0..3] and Q[0..2] are free for the next stage's data from the middle of the stage
+    // on, Q[3] and P[4..7] at its end; the wavefronts meet in the middle, where the next stage's
+    // data has landed.
     static_assert(NS >= 2 && (NS - 1) * LPS < 64, "outstanding loads must fit the wait counter");
-    bf16x8 pfr[2][4], qfr[2][NB];
-    // fragment u of a slice in the order in which the MFMAs first use them: P0, Q0 .. Q(NB-1), P1, P2, P3
-    // byte offset, within a stage, of the first of the two transposing reads of fragment j at slice 0
-    // (NTile::frag); a slice further down is 16 K rows = 8192 bytes on, the second read 4 K rows = 2048.
-    int foff[NF];
-    {
-        const int krl = 8 * (lane >> 5) + ((lane & 15) >> 2);
-        const int cl = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    bf16x8 pfr[NA], qfr[NB];
+    int foff_p[NA], foff_q[NB];
 #pragma unroll
-        for (int j = 0; j < NF; j++)
-            foff[j] = j < 4 ? PT::off(krl, wm * 128 + j * 32 + cl) : PBYTES + PT::off(krl, wn * CW + (j - 4) * 32 + cl);
-    }
-    static_assert(PT::CPR * 16 * 16 == 8192 && PT::CPR * 16 * 4 == 2048, "slice and second-read strides");
-    auto frag_load = [&](int stage, int ks, int buf, int u) {
-        const int j = u == 0 ? 0 : (u <= NB ? 3 + u : u - NB);
-        const char* b = smem + (stage * STAGE + ks * 8192) + foff[j];
-        if (j < 4) pfr[buf][j] = lds_read_tr8(b, b + 2048);
-        else qfr[buf][j - 4] = lds_read_tr8(b, b + 2048);
+    for (int a = 0; a < NA; a++) foff_p[a] = PT::frag_off(wm * 128 + a * 16, lane);
+#pragma unroll
+    for (int b = 0; b < NB; b++) foff_q[b] = PBYTES + PT::frag_off(wn * CW + b * 16, lane);
+    constexpr int SECOND = 4 * PT::CPR * 16;          // bytes between the two reads of a fragment
+    auto load_p = [&](int stage, int a) {
+        const char* b_ = smem + stage * STAGE + foff_p[a];
+        pfr[a] = lds_read_tr8(b_, b_ + SECOND);
     };
-    auto mfma_one = [&](int buf, int i) {
-        const int a = i / NB, b = i % NB;
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pfr[buf][a], qfr[buf][b], acc[a][b], 0, 0, 0);
+    auto load_q = [&](int stage, int b) {
+        const char* b_ = smem + stage * STAGE + foff_q[b];
+        qfr[b] = lds_read_tr8(b_, b_ + SECOND);
+    };
+    auto mfma_one = [&](int a, int b) {
+        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pfr[a], qfr[b], acc[a][b], 0, 0, 0);
     };
 #ifdef UNIPOOL_PHASE_TIMES
     long long pc_wait = 0, pc_bar = 0;
 #endif
-    // ISSUE: the loads of K block kb-1+NS go out during this stage, into the buffer that stage kb-1
-    // has released, one every other MFMA of the slices ahead of the last (a burst of loads stalls the
-    // issuing wavefronts, MFMAs included, until the address unit's queue has drained; spreading them
-    // over the last slice as well measured slower).  The wavefronts meet ahead of the last slice:
-    // its MFMAs, whose fragments are in registers, cover the fragment loads of the next stage.
+    // ISSUE: the loads of K block kb-1+NS go out during the first half of this stage, into the buffer
+    // that stage kb-1 has released, spaced by three MFMAs (a burst of loads stalls the issuing
+    // wavefronts, MFMAs included, until the address unit's queue has drained).
     auto stage_body = [&](auto issue_c, int kb) {
         constexpr bool ISSUE = decltype(issue_c)::value;
-        const int stage = kb % NS;
-        constexpr int SL = MPS * (KS - 1);             // MFMA slots that carry the loads
-        static_assert(KS >= 2 && LPS * 2 <= SL, "one load per two MFMA slots");
-        static_assert(MPS >= NF, "the last slice covers the next fragment loads");
+        const int stage = kb % NS, nstage = (kb + 1) % NS;
+        static_assert(LPS == 4, "load slots below");
         if constexpr (ISSUE) next_block();
 #pragma unroll
-        for (int ks = 0; ks < KS - 1; ks++) {
-#pragma unroll
-            for (int i = 0; i < MPS; i++) {
-                mfma_one(ks & 1, i);
-                if (i < NF) frag_load(stage, ks + 1, (ks + 1) & 1, i);
-                if constexpr (ISSUE) {
-                    const int slot = ks * MPS + i;
-#pragma unroll
-                    for (int u = 0; u < LPS; u++)
-                        if (u * SL / LPS == slot) issue_one((kb + NS - 1) % NS, u);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+        for (int s = 0; s < 16; s++) {
+            mfma_one(s & 3, s >> 2);
+            if (s == 0) load_q(stage, 3);                       // what the previous stage still held
+            if (s >= 1 && s <= 4) load_p(stage, 3 + s);
+            if constexpr (ISSUE) {
+                if (s >= 5 && (s - 5) % 3 == 0) issue_one((kb + NS - 1) % NS, (s - 5) / 3);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
         if constexpr (ISSUE) ld_r += BK;
-        constexpr int buf = (KS - 1) & 1;
 #ifdef UNIPOOL_PHASE_TIMES
         const long long pw0 = clock64();
 #endif
@@ -1170,9 +1201,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
         pc_bar += clock64() - pw1;
 #endif
 #pragma unroll
-        for (int i = 0; i < MPS; i++) {
-            mfma_one(buf, i);
-            if (i < NF) frag_load((kb + 1) % NS, 0, 0, i);
+        for (int s = 0; s < 16; s++) {
+            mfma_one(4 + (s & 3), s >> 2);
+            if (s < 4) load_p(nstage, s);                       // after the last stage: unused, in bounds
+            else if ((s & 3) == 0) load_q(nstage, (s >> 2) - 1);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -1191,7 +1223,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
     const long long pt_filled = wall_clock64(), pc_filled = clock64();
 #endif
 #pragma unroll
-    for (int j = 0; j < NF; j++) frag_load(0, 0, 0, j);
+    for (int a = 0; a < 4; a++) load_p(0, a);
+#pragma unroll
+    for (int b = 0; b < 3; b++) load_q(0, b);
     {
         stage_body(std::integral_constant<bool, false>{}, 0);       // nb >= 1 here
         int kb = 1;
@@ -1202,7 +1236,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
     const long long pt_looped = wall_clock64(), pc_looped = clock64();
 #endif
 
-    // acc[a][b][r] = out[i = m0 + wm*128 + a*32 + 8*(r/4) + 4*(lane/32) + r%4][j = n0 + wn*CW + b*32 + lane%32]
+    // acc[a][b][r] = out[i = m0 + wm*128 + a*16 + 4*(lane/16) + r][j = n0 + wn*CW + b*16 + lane%16]
     // The 128 x CW block of a wavefront leaves in four passes of 32 rows through a wave-private LDS
     // area (rows of CW floats + 4 of padding), so that every lane stores 16 bytes and a wavefront
     // instruction covers whole row segments of 4*CW bytes; when accumulating, the old values are
@@ -1216,13 +1250,15 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
         const int jw = n0 + wn * CW;          // first column of the wavefront's block
         const bool vec_ok = (g.ndim & 3) == 0 && (reinterpret_cast<size_t>(g.out) & 15) == 0;
 #pragma unroll
-        for (int a = 0; a < 4; a++) {
+        for (int a2 = 0; a2 < NA / 2; a2++) {
 #pragma unroll
-            for (int b = 0; b < NB; b++)
+            for (int ah = 0; ah < 2; ah++)
 #pragma unroll
-                for (int r = 0; r < 16; r++)
-                    stg[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * SLD + b * 32 + (lane & 31)] = acc[a][b][r];
-            const int i_blk = m0 + wm * 128 + a * 32;
+                for (int b = 0; b < NB; b++)
+#pragma unroll
+                    for (int r = 0; r < 4; r++)
+                        stg[(16 * ah + 4 * (lane >> 4) + r) * SLD + b * 16 + (lane & 15)] = acc[2 * a2 + ah][b][r];
+            const int i_blk = m0 + wm * 128 + a2 * 32;
 #pragma unroll 4
             for (int it = 0; it < 32 / RPI; it++) {
                 const int row = it * RPI + lane / LPR;
