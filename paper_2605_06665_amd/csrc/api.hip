@@ -88,7 +88,7 @@ WsLayout ws_layout(const unipool_shape& s) {
     const size_t act = s.dtype == UNIPOOL_BF16 ? 2 : 4;
     size_t o = 0;
     w.zeros = o;       o += 256;
-    w.tile_meta = o;   o += align_up((4096 + 4 * (S / 256 + E + T / 128 + 16)) * sizeof(int32_t));
+    w.tile_meta = o;   o += align_up((4096 + 4 * (S / 256 + 2 * E + T / 128 + 16)) * sizeof(int32_t));
     w.chunk_hist = o;  o += align_up(((T + 63) / 64) * E * sizeof(int32_t));
     w.psum_part = o;   o += align_up(rblocks * E * sizeof(float));
     w.dsigma_part = o; o += align_up(rblocks * E * sizeof(int32_t));   // also holds count partials

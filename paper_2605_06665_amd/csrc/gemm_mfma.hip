@@ -231,6 +231,10 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
         r1 = offsets ? offsets[t + 1] : total_rows;
     }
     const int nt = (r1 - r0 + BM - 1) / BM;
+    // Every expert takes an even number of places in the list (the odd one out is an entry without
+    // rows, which the workgroups skip): the kernels hand out the list in pairs of row tiles that run
+    // side by side and share the weight tile through L2, and a pair must not straddle two experts.
+    const int ns = (nt + 1) & ~1;
     lrows[t] = r1 - r0;
     __syncthreads();
     // Order of the experts in the tile list.  The persistent workgroups walk the list in a fixed
@@ -262,7 +266,7 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
         dense += (v.x < place) + (v.y < place) + (v.z < place) + (v.w < place);
     }
     __syncthreads();
-    if (t < E) ltiles[dense] = nt;
+    if (t < E) ltiles[dense] = ns;
     __syncthreads();
     // exclusive prefix sum of the tiles in list order (inclusive Hillis-Steele scan over 512 entries)
     const int mine = ltiles[t];
@@ -278,13 +282,13 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
     if (t == 0) meta[0] = scan[cur][511];
     if (t >= kSchedBase && t < kSchedBase + 4 * kNumXcd) meta[t] = 0;
     __syncthreads();
-    // The rows of an expert are cut into equal tiles (multiples of 32 rows) rather than into full
-    // tiles plus a remainder: tiles that share an expert's weights then take equally long and stay
-    // in step, so the second reader of a weight tile still finds it in L2.
+    // The rows of an expert are cut into equal tiles (multiples of 16 rows, the MFMA's row count)
+    // rather than into full tiles plus a remainder: tiles that share an expert's weights then take
+    // equally long and stay in step, so the second reader of a weight tile still finds it in L2.
     if (t < E) {
         const int my_first = ltiles[dense];
-        const int per = nt > 0 ? (((r1 - r0 + nt - 1) / nt + 31) / 32) * 32 : 0;
-        for (int i = 0; i < nt; i++) {
+        const int per = nt > 0 ? (((r1 - r0 + nt - 1) / nt + 15) / 16) * 16 : 0;
+        for (int i = 0; i < ns; i++) {
             int32_t* m = meta + kTileBase + 4 * (my_first + i);
             m[0] = t;
             m[1] = r0 + i * per;
@@ -299,10 +303,14 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
 // One 256 x 256 output tile, eight wavefronts (two per SIMD).  Wavefront (wm, wn) owns the 64
 // columns of group wn and every second 32-row strip starting at wm; both wavefronts of a column
 // group sit on the same SIMD, so a SIMD always carries the same share of the tile, however many
-// strips hold rows.  MTV = strips of THIS wavefront that hold rows (0..4); the body is instantiated
-// per MTV so that the K loop is straight-line code and absent strips have no accumulators.
+// strips hold rows.  MTV = strips of THIS wavefront that hold rows (0..4), LH = only the upper 16
+// rows of its last strip do; the body is instantiated per (MTV, LH) so that the K loop is
+// straight-line code and absent rows have no MFMAs.
 // The products are v_mfma_f32_16x16x32_bf16 (at the card's power limit this form sustains about a
 // sixth more than 32x32x16): a strip is two 16-row halves, the 64 columns four 16-column blocks.
+#ifndef XW_ROT
+#define XW_ROT 1
+#endif
 constexpr int kXwWaves = 8;
 constexpr int kXwThreads = kXwWaves * 64;
 
@@ -325,7 +333,7 @@ template <int EPI> struct Staging {
 
 // pre: what the previous tile has already requested for this one (bit 0: X(0) and W(0), bit 1: W(1));
 // g0: number of K stages this workgroup has run before this tile (the LDS buffers rotate on).
-template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL, int MTV>
+template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL, int MTV, bool LH>
 __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef cur, TileRef nxt, int pre,
                                         int g0) {
     constexpr int NW = kXwWaves;
@@ -454,12 +462,15 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     auto xbuf = [&](int kt) { return (kt + x0) & 1; };
     auto wbuf = [&](int kt) { return (kt + w0) % 3; };
     // Fragments of one slice: W block nb (16 columns x 32 indices, the MFMA A operand) and X fragment
-    // a = mh * MTV + tm (16 rows x 32 indices, the B operand), one register set each.  A slice is two
-    // halves of 4 * MTV MFMA slots; slot nb * MTV + tm of the first half takes the upper rows of the
-    // strips (mh = 0), of the second half the lower rows, so X[0 .. MTV) and W[0..2] are free for the
-    // next slice's data during the second half, W[3] and X[MTV .. 2 MTV) at its end.
-    constexpr int NXF = 2 * MTV;
-    constexpr int HM = 4 * MTV;
+    // a (16 rows x 32 indices, the B operand: a < MTV the upper rows of strip a, a >= MTV the lower rows
+    // of strip a - MTV), one register set each.  A slice is two halves; slot nb * MTV + tm of the first
+    // takes the upper rows of the strips, slot nb * M2 + tm of the second the lower rows, so X[0 .. MTV)
+    // and W[0..2] are free for the next slice's data during the second half, W[3] and the other X
+    // fragments at its end.
+    static_assert(!LH || MTV >= 2, "a lone strip is always computed whole");
+    constexpr int M2 = MTV - (LH ? 1 : 0);          // strips whose lower 16 rows are computed
+    constexpr int NXF = MTV + M2;
+    constexpr int HM1 = 4 * MTV, HM2 = 4 * M2;      // MFMA slots of the two halves of a slice
     bf16x8 wfr[4], xfr[NXF > 0 ? NXF : 1];
     // per-lane part of the fragment addresses (rows that are multiples of 16 further down add whole rows)
     const int l16 = lane & 15, lg = lane >> 4;
@@ -481,12 +492,12 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
         }
     };
     auto load_x = [&](int kt, int ks, int a) {
-        const int tm = a % (MTV > 0 ? MTV : 1), mh = a / (MTV > 0 ? MTV : 1);
+        const int tm = a < MTV ? a : a - MTV, mh = a < MTV ? 0 : 1;
         const char* xb = smem + xbuf(kt) * XBYTES;
         xfr[a] = lds_read16(xb + ((wm + 2 * tm) * 32 + 16 * mh) * ROWB + (ks ? koff1 : koff0));
     };
     auto mfma_one = [&](int a, int nb) {
-        const int tm = a % (MTV > 0 ? MTV : 1), mh = a / (MTV > 0 ? MTV : 1);
+        const int tm = a < MTV ? a : a - MTV, mh = a < MTV ? 0 : 1;
         acc[tm][mh][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfr[nb], xfr[a], acc[tm][mh][nb], 0, 0, 0);
     };
     // KTAIL: K is not a multiple of BK; chunks past K come from a page of zeros in both operands
@@ -526,7 +537,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     auto stage_body = [&](auto ix_c, auto iw_c, int kt) {
         constexpr bool IX = decltype(ix_c)::value;
         constexpr bool IW = decltype(iw_c)::value;
-        constexpr int SL = 3 * HM;                    // slots before the meeting point
+        constexpr int SL = 2 * HM1 + HM2;             // slots before the meeting point
         constexpr int H = SL / 2;
         auto slot_loads = [&](int slot) {
             if constexpr (IX) {
@@ -552,27 +563,27 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
         }
         auto first_half = [&](int ks, int slot0) {
 #pragma unroll
-            for (int sl = 0; sl < HM; sl++) {
+            for (int sl = 0; sl < HM1; sl++) {
                 mfma_one(sl % MTV, sl / MTV);
                 if (sl == 0) load_w(kt, ks, 3);                        // what the previous slice still held
-                if (sl >= 1 && sl <= MTV) load_x(kt, ks, MTV + sl - 1);
+                if (sl >= 1 && sl <= M2) load_x(kt, ks, MTV + sl - 1);
                 slot_loads(slot0 + sl);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
         auto second_half = [&](int nkt, int nks, int slot0) {       // (nkt, nks): the slice that follows
 #pragma unroll
-            for (int sl = 0; sl < HM; sl++) {
-                mfma_one(MTV + sl % MTV, sl / MTV);
+            for (int sl = 0; sl < HM2; sl++) {
+                mfma_one(MTV + sl % M2, sl / M2);
                 if (sl < MTV) load_x(nkt, nks, sl);
-                else if (sl % MTV == 0) load_w(nkt, nks, sl / MTV - 1);
+                if (sl >= M2 && sl % M2 == 0) load_w(nkt, nks, sl / M2 - 1);
                 if (slot0 >= 0) slot_loads(slot0 + sl);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
         first_half(0, 0);
-        second_half(kt, 1, HM);
-        first_half(1, 2 * HM);
+        second_half(kt, 1, HM1);
+        first_half(1, HM1 + HM2);
         // X(kt+1) and W(kt+1) must have landed.  Loads complete in issue order and every stage
         // issues X first, so only the W loads of stage kt+2 may remain (NSX = 2: no younger X batch).
 #ifdef UNIPOOL_PHASE_TIMES
@@ -668,6 +679,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
         for (int tm = 0; tm < MTV; tm++)
 #pragma unroll
             for (int mh = 0; mh < 2; mh++) {
+                if (LH && tm == MTV - 1 && mh == 1) continue;
                 const int r_in = (wm + 2 * tm) * 32 + 16 * mh + l16;
                 if (r_in < kRouteRows) {
 #pragma unroll
@@ -684,6 +696,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
         for (int tm = 0; tm < MTV; tm++)
 #pragma unroll
             for (int mh = 0; mh < 2; mh++) {
+                if (LH && tm == MTV - 1 && mh == 1) continue;
                 const int r_in = (wm + 2 * tm) * 32 + 16 * mh + l16;
                 if (r_in < rows) {
                     float* orow = out + (size_t)(row0 + r_in) * g.ldo;
@@ -750,7 +763,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
             // -- registers -> staging rows
             if constexpr (EPI == EPI_STORE) {
 #pragma unroll
-                for (int mh = 0; mh < 2; mh++)
+                for (int mh = 0; mh < (LH && tm == MTV - 1 ? 1 : 2); mh++)
 #pragma unroll
                     for (int nb = 0; nb < 4; nb++) {
                         const int c = 16 * nb + 4 * lg;
@@ -759,7 +772,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
                     }
             } else if constexpr (EPI == EPI_SWIGLU_FWD) {
 #pragma unroll
-                for (int q = 0; q < 4; q++) {
+                for (int q = 0; q < (LH && tm == MTV - 1 ? 2 : 4); q++) {
                     const int mh = q >> 1, nbg = q & 1;       // blocks nbg and 2 + nbg: gate and up of the same columns
                     const int c = 16 * nbg + 4 * lg;
                     char* srow = stg + (16 * mh + l16) * SROW;
@@ -788,7 +801,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
                     if (tm + 1 < MTV) { UNIPOOL_LOAD_AB(tm + 1) }
                 }
 #pragma unroll
-                for (int mh = 0; mh < 2; mh++)
+                for (int mh = 0; mh < (LH && tm == MTV - 1 ? 1 : 2); mh++)
 #pragma unroll
                     for (int nb = 0; nb < 4; nb++) {
                         const int c = 16 * nb + 4 * lg;                 // column inside the wave's 64
@@ -955,7 +968,7 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
     auto next_tile = [&]() {
         TileRef t = {0, 0, 0, 0, 0};
         for (;;) {
-            const int lt = xcd * per_xcd + round * P + (slot + round) % P;
+            const int lt = xcd * per_xcd + round * P + (slot + XW_ROT * round) % P;
             if (lt >= lt_end) return t;
             round++;
             const int grp = lt / per_group;
@@ -982,16 +995,30 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
     const int nk = KTAIL ? (g.K + BK - 1) / BK : g.K / BK;
     TileRef cur = next_tile();
     int pre = 0, g0 = 0;
+#ifdef UNIPOOL_PHASE_TIMES
+    int tile_i_ = 0;
+#endif
     while (cur.valid) {
         const TileRef nxt = next_tile();
-        // strips wm, wm+2, ... of this wavefront that hold rows; every body runs the same barriers
+#ifdef UNIPOOL_PHASE_TIMES
+        if (threadIdx.x == 0 && (g.launch_slot & 3) == 1 && tile_i_ < 8)
+            g_phase_times[768 + (blockIdx.x & 255)][tile_i_] = (unsigned long long)wall_clock64();
+        tile_i_++;
+#endif
+        // strips wm, wm+2, ... of this wavefront that hold rows, and whether the last of them is the
+        // tile's last strip with rows in its upper half only; every body runs the same barriers
         const int strips = (cur.rows + 31) >> 5;
-        switch (max(0, (strips - wm + 1) >> 1)) {
-            case 0: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 0>(g, smem, cur, nxt, pre, g0); break;
-            case 1: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 1>(g, smem, cur, nxt, pre, g0); break;
-            case 2: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 2>(g, smem, cur, nxt, pre, g0); break;
-            case 3: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 3>(g, smem, cur, nxt, pre, g0); break;
-            default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4>(g, smem, cur, nxt, pre, g0); break;
+        const int mtv = max(0, (strips - wm + 1) >> 1);
+        const bool lh = mtv >= 2 && wm + 2 * (mtv - 1) == strips - 1 && (((cur.rows + 15) >> 4) & 1) != 0;
+        switch (2 * mtv + (lh ? 1 : 0)) {
+            case 0: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 0, false>(g, smem, cur, nxt, pre, g0); break;
+            case 2: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 1, false>(g, smem, cur, nxt, pre, g0); break;
+            case 4: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 2, false>(g, smem, cur, nxt, pre, g0); break;
+            case 5: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 2, true>(g, smem, cur, nxt, pre, g0); break;
+            case 6: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 3, false>(g, smem, cur, nxt, pre, g0); break;
+            case 7: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 3, true>(g, smem, cur, nxt, pre, g0); break;
+            case 9: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4, true>(g, smem, cur, nxt, pre, g0); break;
+            default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4, false>(g, smem, cur, nxt, pre, g0); break;
         }
         if constexpr (EPI == EPI_ROUTE) {
             lds_barrier();            // the tile's logits are complete in LDS
