@@ -95,6 +95,11 @@ struct GemmArgs {
     float* psum_part;
     int topk;
     float sigma_c, eps;
+    // Meeting point of the two workgroups that run the two row tiles of an expert side by side (one
+    // zeroed counter per pair of list positions, or null): they start their tiles together, so the
+    // weight tile one of them fetches is still in L2 when the other asks for it.
+    int32_t* pair_cnt;
+    int pair_cap;
 };
 
 // EPI_ROUTE keeps the float logits of a tile of up to 128 tokens in LDS: rows of kRouteLdz floats,
@@ -216,10 +221,15 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
 // ---------------------------------------------------------------------------------------------
 constexpr int kTileBase = 64;
 constexpr int kSchedBase = 16;
+constexpr int kPairSpins = 48;      // polls of the partner's arrival, roughly a microsecond apart
+constexpr int kPairCap = 2048;      // meeting counters behind the tile table
+constexpr int kPairMinK = 4096;     // tiles this long are worth the meeting (its cost: a few microseconds)
 
 __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restrict__ offsets, int E,
                                                           int total_rows, int BM,
-                                                          int32_t* __restrict__ meta) {
+                                                          int32_t* __restrict__ meta, int32_t* __restrict__ pair_cnt) {
+    if (pair_cnt != nullptr)
+        for (int i = threadIdx.x; i < kPairCap; i += 512) pair_cnt[i] = 0;
     __shared__ __attribute__((aligned(16))) int lrows[512];   // rows per expert (0 past E)
     __shared__ __attribute__((aligned(16))) int lkey[512];    // place of an expert in the dealt order
     __shared__ int ltiles[512];           // tiles of the expert at a given place
@@ -316,6 +326,7 @@ constexpr int kXwThreads = kXwWaves * 64;
 
 struct TileRef {
     int valid, expert, row0, rows, nt;
+    int pair;       // index of the meeting counter shared with the partner tile, or -1
 };
 
 // Wavefronts that share one staging region of 32 KiB in the epilogue, per epilogue kind: the staging
@@ -963,10 +974,11 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
     const int P = gridDim.x / kNumXcd;                 // workgroups per XCD (the grid is a multiple of 8)
     const int lt_end = min(total, (xcd + 1) * per_xcd);
     const int wm = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8);        // wavefronts 4..7: odd strips
+    const bool use_pairs = !flat && G == 2 && (per_group & 1) == 0 && g.pair_cnt != nullptr && total / 2 <= g.pair_cap;
     int round = 0;
     // the next tile of this workgroup that holds rows, or valid = 0 at the end of the list
     auto next_tile = [&]() {
-        TileRef t = {0, 0, 0, 0, 0};
+        TileRef t = {0, 0, 0, 0, 0, -1};
         for (;;) {
             const int lt = xcd * per_xcd + round * P + (slot + XW_ROT * round) % P;
             if (lt >= lt_end) return t;
@@ -989,6 +1001,14 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
             t.row0 = g.tile_meta[kTileBase + 4 * mt + 1];
             t.rows = rows;
             t.nt = rem / G;
+            // partner: the other row tile of the pair, same column tile (list position lt ^ 1); the
+            // test reads the same table entries on both sides, so either both wait or neither does
+            if (use_pairs) {
+                const int mt2 = mt ^ 1;
+                if (mt2 < n_mt && g.tile_meta[kTileBase + 4 * mt2 + 2] > 0 &&
+                    g.tile_meta[kTileBase + 4 * mt2] == t.expert)
+                    t.pair = lt >> 1;
+            }
             return t;
         }
     };
@@ -1005,6 +1025,18 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
             g_phase_times[768 + (blockIdx.x & 255)][tile_i_] = (unsigned long long)wall_clock64();
         tile_i_++;
 #endif
+        // Meet the partner (bounded wait: if it is far behind, go on alone and fetch the weights twice).
+        if (cur.pair >= 0) {
+            if (threadIdx.x == 0) {
+                int32_t* c = g.pair_cnt + cur.pair;
+                __hip_atomic_fetch_add(c, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int spin = 0; spin < kPairSpins; spin++) {
+                    if (__hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= 2) break;
+                    __builtin_amdgcn_s_sleep(8);
+                }
+            }
+            lds_barrier();
+        }
         // strips wm, wm+2, ... of this wavefront that hold rows, and whether the last of them is the
         // tile's last strip with rows in its upper half only; every body runs the same barriers
         const int strips = (cur.rows + 31) >> 5;
@@ -1401,8 +1433,13 @@ hipError_t run_ptq(const PtqArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
+// the meeting counters live behind the largest possible tile table (total_rows / 256 + 2 E entries)
+int32_t* pair_counters(int32_t* meta, int E, int total_rows) {
+    return meta + kTileBase + 4 * (total_rows / kBM + 2 * E);
+}
+
 hipError_t build_tiles(const int32_t* offsets, int E, int total_rows, int32_t* meta, hipStream_t st) {
-    build_tiles_kernel<<<1, 512, 0, st>>>(offsets, E, total_rows, kBM, meta);
+    build_tiles_kernel<<<1, 512, 0, st>>>(offsets, E, total_rows, kBM, meta, pair_counters(meta, E, total_rows));
     return hipGetLastError();
 }
 
@@ -1475,6 +1512,7 @@ hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_
     b.W = (const bf16*)wd; b.w_stride = (long long)d * f; b.ldw = f;
     b.K = f; b.N = d; b.n_tiles_n = cdiv(d, kBN);
     b.tile_meta = tile_meta; b.launch_slot = 1; b.out0 = y; b.ldo = d;
+    if (b.K >= kPairMinK) { b.pair_cnt = pair_counters(tile_meta, s.E, S); b.pair_cap = kPairCap; }
     return run_xw<true, EPI_STORE>(b, max_tiles, st);
 }
 
@@ -1498,6 +1536,7 @@ hipError_t mfma_ffn_dgrad(const unipool_shape& s, const void* dy, const void* a_
     b.W = (const bf16*)wgu; b.w_stride = 2LL * f * d; b.ldw = d;
     b.K = 2 * f; b.N = d; b.n_tiles_n = cdiv(d, kBN);
     b.tile_meta = tile_meta; b.launch_slot = 1; b.out0 = dx; b.ldo = d;
+    if (b.K >= kPairMinK) { b.pair_cnt = pair_counters(tile_meta, s.E, S); b.pair_cap = kPairCap; }
     return run_xw<false, EPI_STORE>(b, max_tiles, st);
 }
 
