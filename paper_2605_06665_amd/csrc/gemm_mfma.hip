@@ -386,7 +386,8 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
 
     // ---- per-lane source pointers of the direct-to-LDS loads ----------------------------------
     // Load i of a wavefront fills LDS chunks (i*NW + wave)*64 .. +63: 8 rows of 128 bytes.  Loads
-    // whose rows lie in strips without rows are left out (xload[i] false, wave-uniform).
+    // past the tile's last row are left out (xload[i] false, wave-uniform): what the MFMAs then read
+    // for those rows is stale, and it only reaches output rows that are never stored.
     const char* xsrc[XI];
     bool xload[XI];
     const char* wsrc[WI];
@@ -394,7 +395,6 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     auto set_sources = [&](int t_expert, int t_row0, int t_rows, int t_nt) {
         const bf16* We = g.W + (long long)t_expert * g.w_stride;
         const int t_n0 = t_nt * BN, t_f0 = t_nt * (BN / 2);
-        const int t_strips = (t_rows + 31) >> 5;
 #pragma unroll
         for (int i = 0; i < XI; i++) {
             const int q = (i * NW + wave) * 64 + lane;
@@ -402,7 +402,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
             const int cc = (q % XT::CPR) ^ XT::swz(row);
             const int grow = t_row0 + min(row, t_rows - 1);
             xsrc[i] = reinterpret_cast<const char*>(g.X + (size_t)grow * g.ldx + cc * 8);
-            xload[i] = ((i * NW + wave) * 64 / XT::CPR) < t_strips * 32;
+            xload[i] = ((i * NW + wave) * 64 / XT::CPR) < ((t_rows + 7) & ~7);
         }
         if constexpr (WK) {
 #pragma unroll
