@@ -28,6 +28,10 @@ CASES = {
                           c=3.2, skew="zipf"),
     "bf16-smallE": W.Workload("bf16-smallE", L=1, E=10, d=64, f=128, k=3, T=90, dtype="bf16", seed=17,
                               c=2.0),
+    # long reductions in the down projection and in dX (the launches in which the two row tiles of an
+    # expert meet at every tile), experts of one and of two row tiles, rows not multiples of 16
+    "bf16-longk": W.Workload("bf16-longk", L=1, E=6, d=128, f=4096, k=2, T=900, dtype="bf16", seed=18,
+                             c=1.9, skew="hot"),
 }
 CASE_IDS = list(CASES)
 
