@@ -1,4 +1,4 @@
-// bfloat16 grouped GEMMs on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), float accumulate.
+// bfloat16 grouped GEMMs on the CDNA4 matrix cores (v_mfma_f32_16x16x32_bf16), float accumulate.
 //
 // Two kernels cover every dense contraction of the layer:
 //
@@ -8,21 +8,22 @@
 //              possibly chained over several layers; weight gradients)
 //
 // Common structure
-//   * One workgroup per CU: 8 wavefronts (gemm_xw) or 4 with the accumulators in the upper register
-//     file (gemm_ptq).
-//   * Operand tiles go global -> LDS directly (global_load_lds_dwordx4), NS stages deep, one
-//     barrier per K step.  The loads are issued through inline assembly so that the wait counts
+//   * One workgroup of 8 wavefronts per CU, a 256 x 256 output tile, 128 accumulator registers per
+//     lane; fragments have one register set each and are refilled in place as their last use passes.
+//   * Operand tiles go global -> LDS directly (global_load_lds_dwordx4), several stages deep, one
+//     barrier per stage.  The loads are issued through inline assembly so that the wait counts
 //     are ours: the compiler would otherwise wait for every outstanding load before any LDS read.
 //   * LDS tiles hold 16-byte chunks in XOR-swizzled positions; a direct-to-LDS load writes 64
 //     consecutive chunks, so the swizzle is applied on the global address of each lane.
-//   * Operands whose reduction index is the strided one in memory are read from LDS with
-//     ds_read_b64_tr_b16, which hands each lane four consecutive reduction indices of one column.
+//   * Operands whose reduction index is the strided one in memory are read from LDS with pairs of
+//     ds_read_b64_tr_b16, each of which hands a lane four consecutive reduction indices of one column.
 //   * The weight fragment is the MFMA A operand and the activation fragment the B operand, so a
 //     lane ends up with four consecutive output columns of one row: results are staged through
 //     LDS and leave the CU as 16-byte row segments.
 //   * Row groups come from a device-side tile table; nothing is read back to the host.  Tiles are
 //     walked in a fixed order that keeps the tiles of one expert on one XCD (workgroup ids are dealt
-//     round-robin to the 8 XCDs, each of which has its own L2) and lets a workgroup request the first
+//     round-robin to the 8 XCDs, each of which has its own L2), runs the two row tiles of an expert
+//     side by side so that they share its weight tiles in L2, and lets a workgroup request the first
 //     stages of its next tile before the epilogue of the current one.
 #include <type_traits>
 
@@ -174,22 +175,8 @@ template <int BK> struct KTile {
     }
 };
 
-// N-contiguous tile: BK rows of BC elements, CPR = BC/8 chunks per row (>= 16).
-template <int BC> struct NTile {
-    static constexpr int CPR = BC / 8;
-    __device__ static __forceinline__ int swz(int krow) { return (krow & 3) << 2; }
-    __device__ static __forceinline__ int off(int krow, int col) {
-        return (krow * CPR + ((col >> 3) ^ swz(krow))) * 16 + (col & 7) * 2;
-    }
-    // fragment of 32 columns starting at col0, reduction indices ks*16 .. ks*16+15
-    __device__ static __forceinline__ bf16x8 frag(const char* base, int ks, int col0, int lane) {
-        const int krow = ks * 16 + 8 * (lane >> 5) + ((lane & 15) >> 2);
-        const int col = col0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-        return lds_read_tr8(base + off(krow, col), base + off(krow + 4, col));
-    }
-};
-
-// N-contiguous tile read for v_mfma_f32_16x16x32_bf16: a fragment is 16 columns x 32 reduction
+// N-contiguous tile: BK rows of BC elements, CPR = BC/8 chunks per row (>= 16), read for
+// v_mfma_f32_16x16x32_bf16: a fragment is 16 columns x 32 reduction
 // indices; lane l ends with column l%16 and indices 8*(l/16) .. +7.  Two transposing reads (K rows
 // krow and krow+4) of the 4 x 16 block that a group of 16 lanes addresses.  The swizzle keeps the four
 // K rows of a group and the groups 8 rows apart in different banks.
@@ -216,11 +203,10 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// tile table: [0] = number of row tiles; [16 .. 48) = spare words, zeroed here; entry i at
-// kTileBase + 4i: expert, first row, rows in tile
+// tile table: [0] = number of entries; entry i at kTileBase + 4i: expert, first row, rows in tile
+// (0 for the entry that pads an expert to an even number of places)
 // ---------------------------------------------------------------------------------------------
 constexpr int kTileBase = 64;
-constexpr int kSchedBase = 16;
 constexpr int kPairSpins = 48;      // polls of the partner's arrival, roughly a microsecond apart
 constexpr int kPairCap = 2048;      // meeting counters behind the tile table
 constexpr int kPairMinK = 4096;     // tiles this long are worth the meeting (its cost: a few microseconds)
@@ -290,7 +276,6 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
     }
     ltiles[t] = scan[cur][t] - mine;      // first tile of the expert at place t
     if (t == 0) meta[0] = scan[cur][511];
-    if (t >= kSchedBase && t < kSchedBase + 4 * kNumXcd) meta[t] = 0;
     __syncthreads();
     // The rows of an expert are cut into equal tiles (multiples of 16 rows, the MFMA's row count)
     // rather than into full tiles plus a remainder: tiles that share an expert's weights then take
@@ -318,9 +303,6 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
 // straight-line code and absent rows have no MFMAs.
 // The products are v_mfma_f32_16x16x32_bf16 (at the card's power limit this form sustains about a
 // sixth more than 32x32x16): a strip is two 16-row halves, the 64 columns four 16-column blocks.
-#ifndef XW_ROT
-#define XW_ROT 1
-#endif
 constexpr int kXwWaves = 8;
 constexpr int kXwThreads = kXwWaves * 64;
 
@@ -980,7 +962,7 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
     auto next_tile = [&]() {
         TileRef t = {0, 0, 0, 0, 0, -1};
         for (;;) {
-            const int lt = xcd * per_xcd + round * P + (slot + XW_ROT * round) % P;
+            const int lt = xcd * per_xcd + round * P + (slot + round) % P;
             if (lt >= lt_end) return t;
             round++;
             const int grp = lt / per_group;
