@@ -1164,7 +1164,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
         const int ii = i < PI ? i : i - PI;
         const unsigned dst = lds0 + stage * STAGE + (i < PI ? 0 : PBYTES) + ((ii * NW + wave) * 64) * 16;
         const int rb = ld_r + 2 * NW * ii;                 // wave-uniform
-        if (ld_r + BK <= ld_end) {
+        if (__builtin_expect(ld_r + BK <= ld_end, 1)) {
             if (i < PI) glds16_s(ld_p + (size_t)rb * g.mdim, voff_p, dst);
             else glds16_s(ld_q + (size_t)rb * g.ndim, voff_q, dst);
         } else {
