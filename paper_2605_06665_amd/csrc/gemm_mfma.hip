@@ -1184,9 +1184,9 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
 
     // Fragments: P block a (rows of the output) and Q block b (columns), one register set each.  A
     // stage is 32 MFMA slots, slot 4b + a in each half (a = 0..3 in the first half, 4..7 in the
-    // second), so P[0..3] and Q[0..2] are free for the next stage's data from the middle of the stage
-    // on, Q[3] and P[4..7] at its end; the wavefronts meet in the middle, where the next stage's
-    // data has landed.
+    // second), so P[0..3] and Q[0..2] become free for the next stage's data during the second half,
+    // Q[3] and P[4..7] at its end; the wavefronts meet in the middle, where the next stage's data has
+    // landed.
     static_assert(NS >= 2 && (NS - 1) * LPS < 64, "outstanding loads must fit the wait counter");
     bf16x8 pfr[NA], qfr[NB];
     int foff_p[NA], foff_q[NB];
@@ -1220,8 +1220,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
 #pragma unroll
         for (int s = 0; s < 16; s++) {
             mfma_one(s & 3, s >> 2);
-            if (s == 0) load_q(stage, 3);                       // what the previous stage still held
-            if (s >= 1 && s <= 4) load_p(stage, 3 + s);
+            // what the previous stage still held; a refill follows the last use of its registers by two
+            // MFMAs or more (measured: refilling at once costs about 50 cycles per stage)
+            if (s == 2) load_q(stage, 3);
+            if (s >= 3 && s <= 6) load_p(stage, 1 + s);
             if constexpr (ISSUE) {
                 if (s >= 5 && (s - 5) % 3 == 0) issue_one((kb + NS - 1) % NS, (s - 5) / 3);
             }
@@ -1244,8 +1246,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
 #pragma unroll
         for (int s = 0; s < 16; s++) {
             mfma_one(4 + (s & 3), s >> 2);
-            if (s < 4) load_p(nstage, s);                       // after the last stage: unused, in bounds
-            else if ((s & 3) == 0) load_q(nstage, (s >> 2) - 1);
+            if (s >= 2 && s < 6) load_p(nstage, s - 2);         // after the last stage: unused, in bounds
+            else if (s >= 6 && (s & 3) == 2) load_q(nstage, (s >> 2) - 1);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
