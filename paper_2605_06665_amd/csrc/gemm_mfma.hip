@@ -193,12 +193,14 @@ template <int BC> struct NTile16 {
     }
 };
 
+// four floats to four bfloat16 (round to nearest even); converting pairs as vectors lets the compiler
+// use one packed conversion per pair instead of a conversion, a shift and an OR per value
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
-    union { bf16 h[4]; uint2 u; } p;
-    p.h[0] = (bf16)a;
-    p.h[1] = (bf16)b;
-    p.h[2] = (bf16)c;
-    p.h[3] = (bf16)d;
+    typedef __attribute__((ext_vector_type(2))) float f32x2v;
+    typedef __attribute__((ext_vector_type(2))) bf16 bf16x2v;
+    union { bf16x2v h[2]; uint2 u; } p;
+    p.h[0] = __builtin_convertvector(f32x2v{a, b}, bf16x2v);
+    p.h[1] = __builtin_convertvector(f32x2v{c, d}, bf16x2v);
     return p.u;
 }
 
