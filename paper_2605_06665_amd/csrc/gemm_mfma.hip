@@ -209,6 +209,7 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
 // (0 for the entry that pads an expert to an even number of places)
 // ---------------------------------------------------------------------------------------------
 constexpr int kTileBase = 64;
+constexpr int kMaxTableExperts = 512;   // build_tiles_kernel: one thread per expert
 constexpr int kPairSpins = 48;      // polls of the partner's arrival, roughly a microsecond apart
 constexpr int kPairCap = 2048;      // meeting counters behind the tile table
 constexpr int kPairMinK = 4096;     // tiles this long are worth the meeting (its cost: a few microseconds)
@@ -1433,7 +1434,9 @@ hipError_t build_tiles(const int32_t* offsets, int E, int total_rows, int32_t* m
 
 
 bool mfma_ffn_supported(const unipool_shape& s) {
-    return s.dtype == UNIPOOL_BF16 && s.d_model % 64 == 0 && s.d_ff % 64 == 0;
+    // the tile table is built by one workgroup with a thread per expert; the weight-gradient kernel
+    // keeps the per-layer row ranges of an expert in LDS
+    return s.dtype == UNIPOOL_BF16 && s.d_model % 64 == 0 && s.d_ff % 64 == 0 && s.E <= kMaxTableExperts;
 }
 
 bool mfma_router_supported(const unipool_shape& s) {
