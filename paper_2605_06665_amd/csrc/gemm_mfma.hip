@@ -439,15 +439,10 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     const int nk = KTAIL ? (g.K + BK - 1) / BK : g.K / BK;
     // ---- software pipeline ----------------------------------------------------------------------
     // LDS holds NSX stages of the X tile and NSW stages of the W tile (BK reduction indices each).
-    // X rows are shared by all column tiles of an expert and come from L2; W tiles are used by the
-    // one or two row tiles of an expert only and mostly come from HBM, so W is fetched one stage
-    // further ahead than X.  While stage kt is multiplied, X(kt+1) and W(kt+1), W(kt+2) are landing.
-    // A stage is KS slices of 16 indices; fragments are double buffered in registers, and the LDS
-    // reads of the next slice are interleaved one by one with the MFMAs of the current slice
-    // (issue is in order: a burst of LDS reads would hold back the MFMAs behind it).  In the last
-    // slice of a stage the wavefronts meet once: stage kt+1 has landed, nobody reads stage kt any
-    // more, so its buffers take the loads of X(kt+NSX) and W(kt+NSW), whose instructions are again
-    // spread between the MFMAs.
+    // While stage kt is multiplied, X(kt+1), W(kt+1) and W(kt+2) are landing, and from its meeting
+    // point on X(kt+2) as well.  A stage is KS slices of 32 indices; every fragment has one register
+    // set, and the LDS reads that refill it are interleaved one by one with the MFMAs (issue is in
+    // order: a burst of LDS reads would hold back the MFMAs behind it).
     constexpr int NSX = NS, NSW = NS + 1;
     constexpr int WBASE = NSX * XBYTES;
     static_assert(NSX == 2 && NSW == 3, "buffer rotation and wait counts below");
@@ -522,40 +517,33 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
             if (kt * BK + wk[i] >= g.K) src = reinterpret_cast<const char*>(g.zeros);
         glds16(src, lds0 + WBASE + wbuf(kb) * WBYTES + ((i * NW + wave) * 64) * 16);
     };
-    // One stage.  IX / IW: the loads of X(kt+1) / W(kt+2) go out during this stage, into the buffers
-    // that stage kt-1 has released.  They are spread over the MFMA slots before the meeting point, X in
-    // the first half (it has to land within this stage) and W in the second: a wavefront whose load
-    // finds the address unit's queue full stands still, MFMAs included, so a burst of loads from all
-    // wavefronts at once would cost the matrix cores the whole time the queue takes to drain.  The
-    // wavefronts meet between the halves of the second slice: stage kt+1 has landed, nobody reads
-    // stage kt any more, and the second half, whose operands are in registers, covers the first
-    // fragment loads of stage kt+1.
-    auto stage_body = [&](auto ix_c, auto iw_c, int kt) {
-        constexpr bool IX = decltype(ix_c)::value;
+    // One stage.  The wavefronts meet between the halves of the second slice: stage kt+1 has landed,
+    // nobody reads stage kt any more, and the second half, whose operands are in registers, covers the
+    // first fragment loads of stage kt+1.  Loads go out two stages ahead, into the buffers that the
+    // meeting points release: W(kt+2), whose buffer stage kt-1 held, during the MFMAs ahead of the
+    // meeting (IW), X(kt+2), whose buffer is the one stage kt is reading, right behind it.  They are
+    // spread between the MFMAs: a wavefront whose load finds the address unit's queue full stands
+    // still, MFMAs included, so a burst of loads from all wavefronts at once would cost the matrix
+    // cores the whole time the queue takes to drain.
+    auto stage_body = [&](auto iw_c, int kt) {
         constexpr bool IW = decltype(iw_c)::value;
         constexpr int SL = 2 * HM1 + HM2;             // slots before the meeting point
-        constexpr int H = SL / 2;
-        auto slot_loads = [&](int slot) {
-            if constexpr (IX) {
-#pragma unroll
-                for (int u = 0; u < XI; u++)
-                    if (u * H / XI == slot) issue_x(kt + 1, u, kt + 1);
-            }
+        const bool ix = kt + 2 < nk;                  // X(kt+2) exists
+        auto w_loads = [&](int slot) {
             if constexpr (IW) {
 #pragma unroll
                 for (int u = 0; u < WI; u++)
-                    if (H + u * (SL - H) / WI == slot) issue_w(kt + 2, u, kt + 2);
+                    if (u * SL / WI == slot) issue_w(kt + 2, u, kt + 2);
             }
         };
-        if constexpr (SL == 0) {
-            if constexpr (IX) {
+        auto x_loads = [&](int slot) {
 #pragma unroll
-                for (int u = 0; u < XI; u++) issue_x(kt + 1, u, kt + 1);
-            }
-            if constexpr (IW) {
+            for (int u = 0; u < XI; u++)
+                if (u * HM2 / XI == slot && ix) issue_x(kt + 2, u, kt + 2);
+        };
+        if constexpr (SL == 0 && IW) {
 #pragma unroll
-                for (int u = 0; u < WI; u++) issue_w(kt + 2, u, kt + 2);
-            }
+            for (int u = 0; u < WI; u++) issue_w(kt + 2, u, kt + 2);
         }
         auto first_half = [&](int ks, int slot0) {
 #pragma unroll
@@ -563,7 +551,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
                 mfma_one(sl % MTV, sl / MTV);
                 if (sl == 0) load_w(kt, ks, 3);                        // what the previous slice still held
                 if (sl >= 1 && sl <= M2) load_x(kt, ks, MTV + sl - 1);
-                slot_loads(slot0 + sl);
+                w_loads(slot0 + sl);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
@@ -573,15 +561,16 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
                 mfma_one(MTV + sl % M2, sl / M2);
                 if (sl < MTV) load_x(nkt, nks, sl);
                 if (sl >= M2 && sl % M2 == 0) load_w(nkt, nks, sl / M2 - 1);
-                if (slot0 >= 0) slot_loads(slot0 + sl);
+                if (slot0 >= 0) w_loads(slot0 + sl);
+                else x_loads(sl);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
         first_half(0, 0);
         second_half(kt, 1, HM1);
         first_half(1, HM1 + HM2);
-        // X(kt+1) and W(kt+1) must have landed.  Loads complete in issue order and every stage
-        // issues X first, so only the W loads of stage kt+2 may remain (NSX = 2: no younger X batch).
+        // X(kt+1) and W(kt+1) must have landed.  Loads complete in issue order, and the only ones
+        // issued after those two batches are the W loads of stage kt+2.
 #ifdef UNIPOOL_PHASE_TIMES
         PHASE_CLOCK(c0_);
 #endif
@@ -596,6 +585,12 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
         acc_wait_ += c1_ - c0_;
         acc_bar_ += c2_ - c1_;
 #endif
+        if constexpr (HM2 == 0) {
+            if (ix) {
+#pragma unroll
+                for (int u = 0; u < XI; u++) issue_x(kt + 2, u, kt + 2);
+            }
+        }
         second_half(kt + 1, 0, -1);                   // after the last stage: unused, in bounds
     };
     // prologue: X(0) W(0) X(1) W(1) W(2), less what the previous tile has requested already
@@ -636,11 +631,10 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
         using T = std::integral_constant<bool, true>;
         using F = std::integral_constant<bool, false>;
         // stage 0: the prologue has issued X(1) and W(2) already
-        stage_body(F{}, F{}, 0);
+        stage_body(F{}, 0);
         int kt = 1;
-        for (; kt + 2 < nk; kt++) stage_body(T{}, T{}, kt);
-        for (; kt + 1 < nk; kt++) stage_body(T{}, F{}, kt);
-        for (; kt < nk; kt++) stage_body(F{}, F{}, kt);
+        for (; kt + 2 < nk; kt++) stage_body(T{}, kt);
+        for (; kt < nk; kt++) stage_body(F{}, kt);
     }
     lds_barrier();   // every wavefront is done with the operand tiles
     PHASE_STAMP(t_looped);
