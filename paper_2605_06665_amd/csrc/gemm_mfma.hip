@@ -1217,10 +1217,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
 #pragma unroll
         for (int s = 0; s < 16; s++) {
             mfma_one(s & 3, s >> 2);
-            // what the previous stage still held; a refill follows the last use of its registers by two
-            // MFMAs or more (measured: refilling at once costs about 50 cycles per stage)
-            if (s == 2) load_q(stage, 3);
-            if (s >= 3 && s <= 6) load_p(stage, 1 + s);
+            if (s == 0) load_q(stage, 3);                       // what the previous stage still held
+            if (s >= 1 && s <= 4) load_p(stage, 3 + s);
             if constexpr (ISSUE) {
                 if (s >= 5 && (s - 5) % 3 == 0) issue_one((kb + NS - 1) % NS, (s - 5) / 3);
             }
@@ -1243,8 +1241,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
 #pragma unroll
         for (int s = 0; s < 16; s++) {
             mfma_one(4 + (s & 3), s >> 2);
-            if (s >= 2 && s < 6) load_p(nstage, s - 2);         // after the last stage: unused, in bounds
-            else if (s >= 6 && (s & 3) == 2) load_q(nstage, (s >> 2) - 1);
+            if (s < 4) load_p(nstage, s);                       // after the last stage: unused, in bounds
+            else if ((s & 3) == 0) load_q(nstage, (s >> 2) - 1);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
