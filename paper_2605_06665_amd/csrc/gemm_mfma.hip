@@ -1084,8 +1084,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
     const int lt = (blockIdx.x % kNumXcd) * per_xcd + slot;
     if (lt >= total) return;
     const int e = lt / per_e;
-    const int m0 = ((lt % per_e) / g.n_tiles) * BM;
-    const int n0 = ((lt % per_e) % g.n_tiles) * BN;
+    // The 32 workgroups of an XCD run 32 consecutive tiles side by side and share their operand blocks
+    // through L2: with the shorter tile axis running fastest the 32 tiles form the squarest block
+    // (about 6 x 5 instead of 2 x 16), which needs the fewest distinct operand blocks.
+    const int idx = lt % per_e;
+    const int m0 = (g.m_tiles <= g.n_tiles ? idx % g.m_tiles : idx / g.n_tiles) * BM;
+    const int n0 = (g.m_tiles <= g.n_tiles ? idx / g.m_tiles : idx % g.n_tiles) * BN;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
