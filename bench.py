@@ -25,10 +25,10 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per gemm_xw launch from rocprofv3 counters (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
 # of the 1 GiB copy below), averaged over the four expert-FFN launches of a layer; see
 # profiles/gemm_counters_C5.txt.  Not measured for the other workloads.
-MEASURED_XW_TRAFFIC_BYTES = {"C5": 5.8e9}
+MEASURED_XW_TRAFFIC_BYTES = {"C5": 5.5e9}
 # The same average from the L2's own request counters (TCC_EA0_RDREQ_sum x 128 B, every read request of these
 # kernels is a 128-byte one, + WRITE_SIZE), same run of bench.py.
-MEASURED_XW_TRAFFIC_BYTES_RDREQ = {"C5": 5.7e9}
+MEASURED_XW_TRAFFIC_BYTES_RDREQ = {"C5": 5.55e9}
 
 
 def parse():
