@@ -1112,9 +1112,12 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
         lds_q[l] = reinterpret_cast<const bf16*>(g.Q[l]);
     }
     __syncthreads();
-    int nb = 0;     // number of K blocks over all layers
-    for (int l = 0; l < g.n_layers; l++)
-        nb += (__builtin_amdgcn_readfirstlane(lds_r1[l] - lds_r0[l]) + BK - 1) / BK;
+    // The rows of expert e in all the layers form one reduction, cut into K blocks of BK rows without
+    // regard to the layers: a block may end one layer's range and begin the next one's, and only the
+    // very last block is filled up with zero rows.
+    int k_total = 0;
+    for (int l = 0; l < g.n_layers; l++) k_total += max(0, __builtin_amdgcn_readfirstlane(lds_r1[l] - lds_r0[l]));
+    const int nb = (k_total + BK - 1) / BK;
     float* otile = g.out + (long long)e * g.out_stride;
     if (nb == 0) {
         if (!g.accumulate) {
@@ -1130,14 +1133,15 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
     // (i*NW + wave)*64 + lane, i.e. K row 2*NW*i + 2*wave + lane/32, chunk position lane%32.  The
     // swizzle depends on bits 0, 1 and 3 of the K row, which are the same for all i.
     static_assert((2 * NW) % 16 == 0, "the K rows of a lane's loads differ by multiples of 16");
+    static_assert(2 * PI == 4, "four loads per K block");
     const int krow0 = 2 * wave + (lane >> 5);
     const int cc = (lane & 31) ^ PT::swz(krow0);
     const int pcol = min(m0 + cc * 8, g.mdim - 8);
     const int qcol = min(n0 + cc * 8, g.ndim - 8);
 
-    // A K block that lies inside the row range is loaded from a wave-uniform row address plus these
-    // per-lane byte offsets (no vector arithmetic per load); the last block of a range selects, lane
-    // by lane, between its row and the page of zeros.
+    // A K block that lies inside one layer's row range is loaded from a wave-uniform row address plus
+    // these per-lane byte offsets (no vector arithmetic per load); a block that runs over the end of a
+    // range finds, lane by lane, the layer and row of its K index, or the page of zeros past the end.
     const unsigned voff_p = ((unsigned)krow0 * (unsigned)g.mdim + (unsigned)pcol) * 2u;
     const unsigned voff_q = ((unsigned)krow0 * (unsigned)g.ndim + (unsigned)qcol) * 2u;
 
@@ -1151,30 +1155,90 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
         const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
         return reinterpret_cast<const bf16*>(((unsigned long long)hi << 32) | lo);
     };
-    auto next_block = [&]() {     // advance to the next non-empty K block
-        while (ld_r >= ld_end) {
-            ld_layer++;
-            ld_r = __builtin_amdgcn_readfirstlane(lds_r0[ld_layer]);
-            ld_end = __builtin_amdgcn_readfirstlane(lds_r1[ld_layer]);
-            ld_p = uniform_ptr(lds_p[ld_layer]);
-            ld_q = uniform_ptr(lds_q[ld_layer]);
+    // The cursor also holds the next layer in which the expert has rows, fetched from LDS when the
+    // cursor moves (once per layer): a block that straddles two layers then needs no LDS access.
+    int nx_layer = -1, nx_r = 0, nx_end = 0;
+    const bf16* nx_p = nullptr;
+    const bf16* nx_q = nullptr;
+    auto fetch_next = [&]() {
+        nx_r = nx_end = 0;
+        while (++nx_layer < g.n_layers) {
+            nx_r = __builtin_amdgcn_readfirstlane(lds_r0[nx_layer]);
+            nx_end = __builtin_amdgcn_readfirstlane(lds_r1[nx_layer]);
+            if (nx_end > nx_r) {
+                nx_p = uniform_ptr(lds_p[nx_layer]);
+                nx_q = uniform_ptr(lds_q[nx_layer]);
+                return;
+            }
+        }
+        nx_layer = g.n_layers;
+        nx_r = nx_end = 0;
+    };
+    fetch_next();
+    auto next_layer = [&]() {     // the cursor moves to the next layer with rows (wave-uniform); false past the last
+        if (nx_layer >= g.n_layers) return false;
+        ld_layer = nx_layer;
+        ld_r = nx_r;
+        ld_end = nx_end;
+        ld_p = nx_p;
+        ld_q = nx_q;
+        fetch_next();
+        return true;
+    };
+    auto next_block = [&]() {     // put the cursor on the first row of the next K block
+        while (ld_r >= ld_end)
+            if (!next_layer()) break;
+    };
+    auto advance_block = [&]() {  // move the cursor BK rows on, from layer to layer
+        int need = BK;
+        for (;;) {
+            const int n = min(ld_end - ld_r, need);
+            if (n > 0) {
+                ld_r += n;
+                need -= n;
+            }
+            if (need == 0 || !next_layer()) break;
         }
     };
-    // load i (0..LPS-1) of the current K block: P rows for i < PI, Q rows after
+    // Per-lane source addresses of the LPS loads of the K block at the cursor (P rows for i < PI, Q
+    // rows after), worked out in one place per block so that the load slots between the MFMAs hold
+    // nothing but the load.
+    const void* blk_src[2 * PI];
+    auto block_sources = [&]() {
+        if (__builtin_expect(ld_r + BK <= ld_end, 1)) {
+#pragma unroll
+            for (int i = 0; i < 2 * PI; i++) {
+                const int rb = ld_r + 2 * NW * (i < PI ? i : i - PI);         // wave-uniform
+                blk_src[i] = i < PI ? reinterpret_cast<const char*>(ld_p + (size_t)rb * g.mdim) + voff_p
+                                    : reinterpret_cast<const char*>(ld_q + (size_t)rb * g.ndim) + voff_q;
+            }
+        } else {
+            // K index j of this lane inside the block: in the rest of the cursor's layer, in the next
+            // layer, or (the next layer being shorter than the block) further on
+            const int rem = ld_end - ld_r, nrows = nx_end - nx_r;
+#pragma unroll
+            for (int i = 0; i < 2 * PI; i++) {
+                const int j = 2 * NW * (i < PI ? i : i - PI) + krow0;
+                const int dim = i < PI ? g.mdim : g.ndim, col = i < PI ? pcol : qcol;
+                const void* src = g.zeros;
+                if (j < rem) src = (i < PI ? ld_p : ld_q) + (size_t)(ld_r + j) * dim + col;
+                else if (j - rem < nrows) src = (i < PI ? nx_p : nx_q) + (size_t)(nx_r + j - rem) * dim + col;
+                int j0 = rem + nrows;
+                for (int lay = nx_layer + 1; j0 < BK && lay < g.n_layers; lay++) {
+                    const int r = __builtin_amdgcn_readfirstlane(lds_r0[lay]);
+                    const int n = min(__builtin_amdgcn_readfirstlane(lds_r1[lay]) - r, BK - j0);
+                    if (n <= 0) continue;
+                    const bf16* base = uniform_ptr(i < PI ? lds_p[lay] : lds_q[lay]);
+                    if (j >= j0 && j < j0 + n) src = base + (size_t)(r + j - j0) * dim + col;
+                    j0 += n;
+                }
+                blk_src[i] = src;
+            }
+        }
+    };
     auto issue_one = [&](int stage, int i) {
         const int ii = i < PI ? i : i - PI;
-        const unsigned dst = lds0 + stage * STAGE + (i < PI ? 0 : PBYTES) + ((ii * NW + wave) * 64) * 16;
-        const int rb = ld_r + 2 * NW * ii;                 // wave-uniform
-        if (__builtin_expect(ld_r + BK <= ld_end, 1)) {
-            if (i < PI) glds16_s(ld_p + (size_t)rb * g.mdim, voff_p, dst);
-            else glds16_s(ld_q + (size_t)rb * g.ndim, voff_q, dst);
-        } else {
-            const int r = rb + krow0;
-            const void* src = g.zeros;
-            if (r < ld_end)
-                src = i < PI ? (const void*)(ld_p + (size_t)r * g.mdim + pcol) : (const void*)(ld_q + (size_t)r * g.ndim + qcol);
-            glds16(src, dst);
-        }
+        glds16(blk_src[i], lds0 + stage * STAGE + (i < PI ? 0 : PBYTES) + ((ii * NW + wave) * 64) * 16);
     };
 
     f32x4 acc[NA][NB];
@@ -1217,7 +1281,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
         constexpr bool ISSUE = decltype(issue_c)::value;
         const int stage = kb % NS, nstage = (kb + 1) % NS;
         static_assert(LPS == 4, "load slots below");
-        if constexpr (ISSUE) next_block();
+        if constexpr (ISSUE) {
+            next_block();
+            block_sources();
+        }
 #pragma unroll
         for (int s = 0; s < 16; s++) {
             mfma_one(s & 3, s >> 2);
@@ -1228,7 +1295,7 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if constexpr (ISSUE) ld_r += BK;
+        if constexpr (ISSUE) advance_block();
 #ifdef UNIPOOL_PHASE_TIMES
         const long long pw0 = clock64();
 #endif
@@ -1254,9 +1321,10 @@ __global__ __launch_bounds__(64 * NW) void gemm_ptq_kernel(const PtqArgs g) {
     for (int s = 0; s < NS; s++)
         if (s < nb) {
             next_block();
+            block_sources();
 #pragma unroll
             for (int i = 0; i < LPS; i++) issue_one(s, i);
-            ld_r += BK;
+            advance_block();
         }
     if (nb > NS - 1) wait_vmcnt<(NS - 1) * LPS>();
     else wait_vmcnt<0>();
