@@ -32,6 +32,11 @@ CASES = {
     # expert meet at every tile), experts of one and of two row tiles, rows not multiples of 16
     "bf16-longk": W.Workload("bf16-longk", L=1, E=6, d=128, f=4096, k=2, T=900, dtype="bf16", seed=18,
                              c=1.9, skew="hot"),
+    # pooled weight gradient: the rows of an expert in the layers are one reduction cut into blocks of 32
+    # rows; here a block takes in several layers (about 6 rows per layer and expert) ...
+    "bf16-deep": W.Workload("bf16-deep", L=6, E=16, d=64, f=128, k=2, T=48, dtype="bf16", seed=19, c=2.2),
+    # ... and here blocks straddle two layers at rows that are no multiples of anything (about 75 rows)
+    "bf16-deep3": W.Workload("bf16-deep3", L=3, E=4, d=128, f=64, k=2, T=150, dtype="bf16", seed=20, c=1.8),
 }
 CASE_IDS = list(CASES)
 
