@@ -183,6 +183,13 @@ def main():
                                   "avg_ms": ms_u, "algorithmic_bytes": by_u,
                                   "mean_distinct_per_token": float(dist_mean.item())}
 
+    # the binding roofline of the average gemm_xw launch: the longer of its MFMA time and its HBM time at
+    # the published peaks (at 341 rows per expert the launch sits below the ridge of 312 FLOP per byte)
+    xw_bytes_per_launch = (12.0 * w.E * w.d * w.f + 8.0 * S * w.d + 20.0 * S * w.f) / 4.0
+    t_mfma_ms = xw_flops_per_launch / (PEAK_BF16_TFLOPS * 1e12) * 1e3
+    t_hbm_ms = xw_bytes_per_launch / (PEAK_HBM_GBS * 1e9) * 1e3
+    binding = {"bound": "hbm" if t_hbm_ms > t_mfma_ms else "mfma", "t_mfma_ms": t_mfma_ms, "t_hbm_ms": t_hbm_ms,
+               "frac": max(t_mfma_ms, t_hbm_ms) / avg_xw_ms}
     out = {
         "metric": "shared-pool MoE layer fwd+bwd tokens/s; grouped-GEMM % bf16 MFMA peak",
         "value": w.L * w.T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
@@ -196,7 +203,8 @@ def main():
                      "frac": xw_tflops / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_XW_TRAFFIC_BYTES.get(a.workload),
                      "traffic_from_l2_read_requests": MEASURED_XW_TRAFFIC_BYTES_RDREQ.get(a.workload),
-                     "algorithmic_bytes_per_launch": (12.0 * w.E * w.d * w.f + 8.0 * S * w.d + 20.0 * S * w.f) / 4.0,
+                     "algorithmic_bytes_per_launch": xw_bytes_per_launch,
+                     "binding_roofline": binding,
                      "kernel": "gemm_xw (grouped bf16 GEMM: gate-up, down, dH, dX)",
                      "avg_launch_ms": avg_xw_ms, "launches": n_xw,
                      "flops_per_launch": xw_flops_per_launch},
