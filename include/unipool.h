@@ -127,6 +127,20 @@ int unipool_permute(const unipool_shape* shape, const void* x, const int32_t* to
                     void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * unipool_permute for callers that cannot allocate or size a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same inputs, outputs, kernels and
+ * results as unipool_permute, but the per-chunk histograms live in a static device array inside the
+ * library (2 MiB per GPU, held until the process ends) instead of the caller's workspace.
+ * Limit: ceil(T/64) * E <= 524288; larger shapes return UNIPOOL_EINVAL (use unipool_permute).
+ * The call allocates nothing; its first call on a device looks up the array's device address.
+ * All calls on one GPU share that array: calls that overlap on one GPU (different streams or
+ * threads) race; order them on one stream.  Nothing of an earlier call is read by a later one.
+ */
+int unipool_permute_static(const unipool_shape* shape, const void* x, const int32_t* topk_idx,
+                           const int32_t* counts, void* x_perm, int32_t* expert_offsets,
+                           int32_t* row_of_slot, int32_t* slot_of_row, void* stream);
+
+/*
  * Pool experts on their row groups (Eq. 2's e_i; SwiGLU FFN, Table 6 caption).
  * For every expert e with rows R_e:  A = X_e W_gate,e^T;  B = X_e W_up,e^T;
  *   H = silu(A) * B;  Y = H W_down,e^T.   Experts without rows cost nothing.

@@ -27,7 +27,7 @@ class Shape(ctypes.Structure):
 
 
 ENTRY_POINTS = ("unipool_workspace_bytes", "unipool_last_error", "unipool_version", "unipool_route",
-                "unipool_route_bwd", "unipool_permute", "unipool_expert_ffn_fwd",
+                "unipool_route_bwd", "unipool_permute", "unipool_permute_static", "unipool_expert_ffn_fwd",
                 "unipool_expert_ffn_recompute", "unipool_expert_ffn_bwd", "unipool_expert_wgrad", "unipool_combine",
                 "unipool_combine_bwd", "unipool_pool_aux_loss", "unipool_estimate_c",
                 "unipool_distinct_experts")
@@ -58,6 +58,7 @@ def load_library():
             "unipool_route": [SP] + [P] * 7 + [P, Z, P],
             "unipool_route_bwd": [SP] + [P] * 9 + [I, P, Z, P],
             "unipool_permute": [SP] + [P] * 7 + [P, Z, P],
+            "unipool_permute_static": [SP] + [P] * 7 + [P],
             "unipool_expert_ffn_fwd": [SP] + [P] * 8 + [P, Z, P],
             "unipool_expert_ffn_recompute": [SP] + [P] * 6 + [P, Z, P],
             "unipool_expert_ffn_bwd": [SP] + [P] * 12 + [P, Z, P],
@@ -144,6 +145,12 @@ def permute(shape, x, topk_idx, counts, x_perm, expert_offsets, row_of_slot, slo
     _check(load_library().unipool_permute(ctypes.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(counts),
                                           _ptr(x_perm), _ptr(expert_offsets), _ptr(row_of_slot),
                                           _ptr(slot_of_row), p, n, _stream(stream)), "unipool_permute")
+
+
+def permute_static(shape, x, topk_idx, counts, x_perm, expert_offsets, row_of_slot, slot_of_row, stream=None):
+    _check(load_library().unipool_permute_static(ctypes.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(counts),
+                                                 _ptr(x_perm), _ptr(expert_offsets), _ptr(row_of_slot),
+                                                 _ptr(slot_of_row), _stream(stream)), "unipool_permute_static")
 
 
 def expert_ffn_fwd(shape, x_perm, expert_offsets, w_gate_up, w_down, act_a, act_b, act_h, y_perm, ws,

@@ -99,9 +99,7 @@ WsLayout ws_layout(const unipool_shape& s) {
     return w;
 }
 
-namespace {
-
-int validate(const unipool_shape* s, const char* fn) {
+int validate_shape(const unipool_shape* s, const char* fn) {
     if (!s) return set_error(UNIPOOL_EINVAL, "%s: shape is NULL", fn);
     if (s->dtype != UNIPOOL_F32 && s->dtype != UNIPOOL_BF16)
         return set_error(UNIPOOL_EINVAL, "%s: dtype %d is neither UNIPOOL_F32 nor UNIPOOL_BF16", fn, s->dtype);
@@ -121,6 +119,8 @@ int validate(const unipool_shape* s, const char* fn) {
     return UNIPOOL_OK;
 }
 
+namespace {
+
 int need_ws(const unipool_shape* s, void* ws, size_t ws_bytes, const char* fn) {
     if (!ws) return set_error(UNIPOOL_EWORKSPACE, "%s: workspace is NULL", fn);
     if (((uintptr_t)ws & 255) != 0) return set_error(UNIPOOL_EWORKSPACE, "%s: workspace is not 256-byte aligned", fn);
@@ -134,7 +134,7 @@ int need_ws(const unipool_shape* s, void* ws, size_t ws_bytes, const char* fn) {
     if (!(p)) return unipool::set_error(UNIPOOL_EINVAL, "%s: argument %s is NULL", __func__, #p)
 #define PROLOGUE()                                                            \
     {                                                                         \
-        int rc_ = unipool::validate(shape, __func__);                         \
+        int rc_ = unipool::validate_shape(shape, __func__);                         \
         if (rc_) return rc_;                                                  \
     }
 #define NEED_WS()                                                             \
@@ -151,7 +151,7 @@ using namespace unipool;
 extern "C" {
 
 size_t unipool_workspace_bytes(const unipool_shape* shape) {
-    if (validate(shape, __func__) != UNIPOOL_OK) return 0;
+    if (validate_shape(shape, __func__) != UNIPOOL_OK) return 0;
     return ws_layout(*shape).total;
 }
 

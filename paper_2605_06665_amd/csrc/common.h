@@ -24,6 +24,8 @@ constexpr int kMaxK = 8;
 // ---- error reporting (host) ------------------------------------------------
 int set_error(int code, const char* fmt, ...);
 int check_hip(hipError_t e, const char* what);
+// Range and alignment checks every entry point runs on its shape before anything is launched.
+int validate_shape(const unipool_shape* s, const char* fn);
 
 // ---- scalar conversions (device) --------------------------------------------
 __device__ __forceinline__ float to_f32(float v) { return v; }

@@ -11,6 +11,8 @@
 //                the rank of the token inside its chunk is the number of lower tokens that
 //                selected the same expert (a ballot and a popcount); row = chunk base + rank.
 //                The row is read once and written k times with 16-byte accesses.
+#include <mutex>
+
 #include "kernels.h"
 
 namespace unipool {
@@ -18,6 +20,34 @@ namespace unipool {
 namespace {
 
 constexpr int kChunkWaves = 4;   // chunks (wavefronts) per block
+
+// Scratch of unipool_permute_static: the per-chunk histograms / base rows ([ceil(T/64)][E] int32) that
+// unipool_permute keeps in the caller's workspace.  One copy per GPU, held until the process ends.
+constexpr size_t kStaticHistWords = 512 * 1024;       // 2 MiB: e.g. T = 65536 with E = 512
+static __device__ __align__(256) int32_t scratch[kStaticHistWords];
+
+// Device address of `scratch` on the current device (the array's name is only a host-side handle of
+// the symbol; every GPU holds its own copy at its own address).  Looked up once per device.
+constexpr int kMaxDevices = 64;
+int32_t* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+hipError_t scratch_address(int32_t** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 __device__ __forceinline__ void build_masks(unsigned long long* mask, const int32_t* topk_idx,
                                             int t, int T, int E, int k, int lane, int* sel) {
@@ -198,3 +228,25 @@ hipError_t launch_permute(const unipool_shape& s, const void* x, const int32_t* 
 }
 
 }  // namespace unipool
+
+extern "C" int unipool_permute_static(const unipool_shape* shape, const void* x, const int32_t* topk_idx,
+                                      const int32_t* counts, void* x_perm, int32_t* expert_offsets,
+                                      int32_t* row_of_slot, int32_t* slot_of_row, void* stream) {
+    using namespace unipool;
+    int rc = validate_shape(shape, __func__);
+    if (rc) return rc;
+    if (!x || !topk_idx || !counts || !x_perm || !expert_offsets || !row_of_slot || !slot_of_row)
+        return set_error(UNIPOOL_EINVAL, "%s: a tensor argument is NULL", __func__);
+    const size_t words = (size_t)cdiv(shape->T, 64) * (size_t)shape->E;
+    if (words > kStaticHistWords)
+        return set_error(UNIPOOL_EINVAL, "%s: ceil(T/64)*E = %zu exceeds the static scratch of %zu words; use unipool_permute",
+                         __func__, words, kStaticHistWords);
+    int32_t* hist = nullptr;
+    hipError_t e = scratch_address(&hist);
+    if (e != hipSuccess) return check_hip(e, "unipool_permute_static: address of the static scratch");
+    // every word of the histogram region in use is written by the first kernel before it is read:
+    // nothing of an earlier call survives into this one
+    return check_hip(launch_permute(*shape, x, topk_idx, counts, x_perm, expert_offsets, row_of_slot,
+                                    slot_of_row, hist, (hipStream_t)stream),
+                     "unipool_permute_static");
+}
