@@ -7,7 +7,7 @@ import pytest
 
 from oracle import unipool_oracle as O
 from synth import workloads as W
-from tests.gpu_util import TOL, dev, host, near_tie_tokens, rel_err
+from tests.gpu_util import TOL, check_selection, dev, host, rel_err
 from tests.test_gpu_parity import CASES, empty, lib, oracle_case, pack_gate_up, shape_of, workspace, _ffn_inputs
 
 pytestmark = pytest.mark.gpu
@@ -107,11 +107,7 @@ def test_lagged_loop_against_the_oracle(name):
         idxs = []
         for l in range(w.L):
             z = O.router_logits(batches[m][0][l], c["wrs"][l])
-            ref_idx = O.topk_select(z, w.k)
-            gi = host(ps.layers[l].topk_idx)
-            tie = near_tie_tokens(z, w.k)
-            assert np.array_equal(gi[~tie], ref_idx[~tie])
-            ref_idx[tie] = gi[tie]
+            _, ref_idx = check_selection(z, O.topk_select(z, w.k), host(ps.layers[l].topk_idx), w.k)
             idxs.append(ref_idx)
         ref = O.pool_step(batches[m][0], c["wrs"], c["wg"], c["wu"], c["wd"], batches[m][1], w.k, c["sigmas"],
                           w.c, w.eps, w.alpha, fbar_in=fbar_ref, idxs=idxs)
@@ -156,11 +152,7 @@ def test_layer_aux_on_the_shared_pool(name):
     idxs = []
     for l in range(w.L):
         z = O.router_logits(c["xs"][l], c["wrs"][l])
-        ref_idx = O.topk_select(z, w.k)
-        gi = host(ps.layers[l].topk_idx)
-        tie = near_tie_tokens(z, w.k)
-        assert np.array_equal(gi[~tie], ref_idx[~tie])
-        ref_idx[tie] = gi[tie]
+        _, ref_idx = check_selection(z, O.topk_select(z, w.k), host(ps.layers[l].topk_idx), w.k)
         idxs.append(ref_idx)
     ref = O.pool_step(c["xs"], c["wrs"], c["wg"], c["wu"], c["wd"], c["gs"], w.k, c["sigmas"], w.c, w.eps,
                       w.alpha, idxs=idxs, aux="layer")
@@ -195,11 +187,7 @@ def test_sharing_scope_two_groups(name):
     groups = []
     for g in range(2):
         z = O.router_logits(c["xs"][g], c["wrs"][g])
-        ref_idx = O.topk_select(z, w.k)
-        gi = host(pg.groups[g].layers[0].topk_idx)
-        tie = near_tie_tokens(z, w.k)
-        assert np.array_equal(gi[~tie], ref_idx[~tie])
-        ref_idx[tie] = gi[tie]
+        _, ref_idx = check_selection(z, O.topk_select(z, w.k), host(pg.groups[g].layers[0].topk_idx), w.k)
         r = O.pool_step([c["xs"][g]], [c["wrs"][g]], *pools[g], [c["gs"][g]], w.k, [c["sigmas"][g]], w.c, w.eps,
                         w.alpha, idxs=[ref_idx])
         groups.append(r)

@@ -10,7 +10,7 @@ import pytest
 
 from oracle import unipool_oracle as O
 from synth import workloads as W
-from tests.gpu_util import TOL, dev, host, near_tie_tokens, rel_err, round_act
+from tests.gpu_util import TOL, check_selection, dev, host, near_tie_tokens, rel_err, round_act
 
 pytestmark = pytest.mark.gpu
 
@@ -37,6 +37,13 @@ CASES = {
     "bf16-deep": W.Workload("bf16-deep", L=6, E=16, d=64, f=128, k=2, T=48, dtype="bf16", seed=19, c=2.2),
     # ... and here blocks straddle two layers at rows that are no multiples of anything (about 75 rows)
     "bf16-deep3": W.Workload("bf16-deep3", L=3, E=4, d=128, f=64, k=2, T=150, dtype="bf16", seed=20, c=1.8),
+    # degenerate shapes: every expert selected (k = E), a single token, fewer tokens than a wavefront with
+    # a pool beyond the fused router's 256 experts
+    "f32-kE": W.Workload("f32-kE", L=2, E=4, d=40, f=24, k=4, T=50, dtype="f32", seed=21, c=1.2),
+    "bf16-kE": W.Workload("bf16-kE", L=1, E=8, d=64, f=64, k=8, T=100, dtype="bf16", seed=22, c=1.1),
+    "bf16-T1": W.Workload("bf16-T1", L=2, E=16, d=64, f=64, k=2, T=1, dtype="bf16", seed=23, c=2.6),
+    "bf16-fewtok-bigE": W.Workload("bf16-fewtok-bigE", L=1, E=320, d=64, f=64, k=4, T=40, dtype="bf16", seed=24,
+                                   c=3.0),
 }
 CASE_IDS = list(CASES)
 
@@ -96,13 +103,9 @@ def test_route(name):
     torch.cuda.synchronize()
     tol = TOL[w.dtype]
     assert rel_err(host(logits), ref["z"]) <= tol
-    tie = near_tie_tokens(ref["z"], w.k)
-    ok = ~tie
     gi = host(idx)
-    assert np.array_equal(gi[ok], ref["idx"][ok]), "top-k indices differ outside near-ties"
-    assert rel_err(host(gate)[ok], ref["gate"][ok]) <= tol
-    # near-tie tokens must still hold k distinct valid experts
-    assert all(len(set(r)) == w.k and 0 <= min(r) and max(r) < w.E for r in gi[tie].tolist())
+    # bit-exact outside near-ties; on near-tie tokens a valid choice (see check_selection); gates of all tokens
+    tie, _ = check_selection(ref["z"], ref["idx"], gi, w.k, scores=ref["s"], got_gate=host(gate), tol=tol)
     assert np.array_equal(host(counts), np.bincount(gi.ravel(), minlength=w.E))
     if np.array_equal(gi, ref["idx"]):
         assert np.array_equal(host(counts), ref["counts"])
@@ -320,12 +323,8 @@ def test_whole_step(name, wgrad):
     n_tie = 0
     for l in range(w.L):
         z = O.router_logits(c["xs"][l], c["wrs"][l])
-        ref_idx = O.topk_select(z, w.k)
-        gi = host(ps.layers[l].topk_idx)
-        tie = near_tie_tokens(z, w.k)
-        assert np.array_equal(gi[~tie], ref_idx[~tie])
+        tie, ref_idx = check_selection(z, O.topk_select(z, w.k), host(ps.layers[l].topk_idx), w.k)
         n_tie += int(tie.sum())
-        ref_idx[tie] = gi[tie]
         idxs.append(ref_idx)
     ref = O.pool_step(c["xs"], c["wrs"], c["wg"], c["wu"], c["wd"], c["gs"], w.k, c["sigmas"], w.c, w.eps,
                       w.alpha, idxs=idxs)
@@ -341,7 +340,11 @@ def test_whole_step(name, wgrad):
         assert rel_err(host(st.out), fw["out"]) <= tol2, "out"
         assert rel_err(host(st.dx), bw["dx"]) <= tol2, "dx"
         assert rel_err(host(st.d_w_router), bw["dw_router"]) <= tol2, "dw_router"
-        assert abs(float(host(st.d_sigma)[0]) - bw["dsigma"]) <= tol2 * max(abs(bw["dsigma"]), 1e-3)
+        # d sigma is one sum of S signed terms dgate * gate / sigma (plus the pool-loss terms): its error scale is
+        # the 2-norm of the terms (what a sum of terms with independent rounding errors carries), not the
+        # magnitude the terms happen to cancel to
+        terms = np.linalg.norm(bw["dgate"] * fw["gate"] / c["sigmas"][l])
+        assert abs(float(host(st.d_sigma)[0]) - bw["dsigma"]) <= tol2 * max(abs(bw["dsigma"]), terms, 1e-3)
     assert rel_err(host(ps.d_w_gate_up), np.concatenate([ref["dw_gate"], ref["dw_up"]], axis=1)) <= tol2
     assert rel_err(host(ps.d_w_down), ref["dw_down"]) <= tol2
     # determinism: a second step gives bitwise the same results
