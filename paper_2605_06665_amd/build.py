@@ -15,7 +15,6 @@ LIB_PATH = os.path.join(PKG_DIR, "libunipool.so")
 SOURCES = ["api.hip", "router.hip", "permute.hip", "combine.hip", "aux_loss.hip", "analysis.hip", "gemm_naive.hip",
            "gemm_mfma.hip"]
 
-
 def _hipcc() -> str:
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", shutil.which("hipcc")):
         if cand and os.path.exists(cand):
@@ -26,20 +25,38 @@ def _hipcc() -> str:
 def _flags():
     return ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
-            "-Wno-unused-command-line-argument",
+            "-Wno-unused-command-line-argument", "-Wno-inline-asm",
             "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def _compile(src: str, extra) -> str:
-    obj = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".o")
+_INCREMENTAL = False     # development aid: skip a source whose object is newer than every file in csrc/ and include/
+
+
+def _up_to_date(obj: str) -> bool:
+    if not _INCREMENTAL or not os.path.exists(obj):
+        return False
+    t = os.path.getmtime(obj)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "unipool.h"), __file__]
+    return all(os.path.getmtime(d) < t for d in deps)
+
+
+def _compile(src: str, extra, obj_dir=None) -> str:
+    obj_dir = obj_dir or BUILD_DIR
+    os.makedirs(obj_dir, exist_ok=True)
+    obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+    if _up_to_date(obj):
+        return obj
     cmd = [_hipcc()] + _flags() + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj]
-    r = subprocess.run(cmd, capture_output=True, text=True)
+    r = subprocess.run(cmd, capture_output=True, text=True, cwd=obj_dir)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
     return obj
 
 
-def build(verbose: bool = True, extra_flags=()) -> str:
+def build(verbose: bool = True, extra_flags=(), incremental: bool = False) -> str:
+    """Compiles every source (always, unless incremental is set) and links libunipool.so."""
+    global _INCREMENTAL
+    _INCREMENTAL = bool(incremental)
     os.makedirs(BUILD_DIR, exist_ok=True)
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra_flags), SOURCES))

@@ -16,26 +16,27 @@ size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 size_t align_up_256(size_t v) { return (v + 255) & ~(size_t)255; }
 namespace {
 
-// UNIPOOL_FORCE_NAIVE=1 sends bfloat16 contractions to the plain one-thread-per-element kernels
-// (a debugging aid; still device code).
+// Debugging builds (-DUNIPOOL_DEBUG_SWITCHES) read two switches from the environment; a regular build has
+// none and keeps no state.  UNIPOOL_FORCE_NAIVE=1 sends bfloat16 contractions to the plain
+// one-thread-per-element kernels; UNIPOOL_UNFUSED_ROUTER=1 keeps the logits GEMM and the selection in
+// separate kernels.
+#ifdef UNIPOOL_DEBUG_SWITCHES
+bool env_switch(const char* name) {
+    const char* e = getenv(name);
+    return e && e[0] == '1';
+}
 bool force_naive() {
-    static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("UNIPOOL_FORCE_NAIVE");
-        v = (e && e[0] == '1') ? 1 : 0;
-    }
-    return v == 1;
+    static const bool v = env_switch("UNIPOOL_FORCE_NAIVE");
+    return v;
 }
-
-// UNIPOOL_UNFUSED_ROUTER=1 keeps the logits GEMM and the selection in separate kernels.
 bool unfused_router() {
-    static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("UNIPOOL_UNFUSED_ROUTER");
-        v = (e && e[0] == '1') ? 1 : 0;
-    }
-    return v == 1;
+    static const bool v = env_switch("UNIPOOL_UNFUSED_ROUTER");
+    return v;
 }
+#else
+constexpr bool force_naive() { return false; }
+constexpr bool unfused_router() { return false; }
+#endif
 
 __global__ void fill_zero_kernel(uint32_t* p, size_t words) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

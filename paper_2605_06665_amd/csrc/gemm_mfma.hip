@@ -25,24 +25,12 @@
 //     round-robin to the 8 XCDs, each of which has its own L2), runs the two row tiles of an expert
 //     side by side so that they share its weight tiles in L2, and lets a workgroup request the first
 //     stages of its next tile before the epilogue of the current one.
-#include <type_traits>
-
-#include "kernels.h"
+#include "gemm_common.h"
 #include "route_select.h"
 
 namespace unipool {
 
 namespace {
-
-constexpr int EPI_STORE = 0;       // bf16 store (optionally added to the destination)
-constexpr int EPI_SWIGLU_FWD = 1;  // tile = [gate | up] columns; writes A, B, H = silu(A)*B
-constexpr int EPI_SWIGLU_BWD = 2;  // acc = dH; reads A, B; writes dA | dB
-constexpr int EPI_F32 = 3;         // float store
-constexpr int EPI_ROUTE = 4;       // acc = logits: float store, then NormRouter scores, top-k and statistics
-
-constexpr int kNumXcd = 8;
-
-constexpr int kMaxPtqLayers = 256;   // layers chained in one weight-gradient reduction
 
 // Profiling builds (-DUNIPOOL_PHASE_TIMES) add up, per workgroup, the time the first wavefront
 // spends in the three phases of a gemm_xw tile (100 MHz ticks): pipeline fill, K loop, epilogue; one row per
@@ -67,41 +55,6 @@ __device__ unsigned long long g_phase_times[1024][8];
 #define PHASE_COMMIT(t0, t1, t2, t3)
 #endif
 
-struct GemmArgs {
-    const bf16* X;
-    int ldx;
-    const bf16* W;
-    long long w_stride;   // elements between experts
-    int ldw;
-    int K, N;             // reduction length; number of output columns (per half for SWIGLU_FWD)
-    int n_tiles_n;
-    int32_t* tile_meta;
-    int launch_slot;      // ordinal of the launch inside its entry point (profiling builds file phase times by it)
-    void* out0;
-    void* out1;
-    void* out2;
-    int ldo;
-    int add;              // EPI_STORE: add to the destination
-    const bf16* aux_a;
-    const bf16* aux_b;
-    int up_rows;          // EPI_SWIGLU_FWD: row offset of the up projection inside W_e (= d_ff)
-    int group_m;          // row tiles walked together
-    const void* zeros;    // >= 16 readable zero bytes (reduction tail of KTAIL kernels)
-    // ungrouped matrices (router): flat_rows > 0 replaces the tile table by row tiles of flat_bm rows
-    int flat_rows, flat_bm;
-    // EPI_ROUTE: outputs of the selection and its constants
-    int32_t* topk_idx;
-    float* topk_gate;
-    int32_t* cnt_part;
-    float* psum_part;
-    int topk;
-    float sigma_c, eps;
-    // Meeting point of the two workgroups that run the two row tiles of an expert side by side (one
-    // zeroed counter per pair of list positions, or null): they start their tiles together, so the
-    // weight tile one of them fetches is still in L2 when the other asks for it.
-    int32_t* pair_cnt;
-    int pair_cap;
-};
 
 // EPI_ROUTE keeps the float logits of a tile of up to 128 tokens in LDS: rows of kRouteLdz floats,
 // then the score sums of the eight wavefronts and the selection counts of the two 64-token blocks.
@@ -112,110 +65,10 @@ constexpr int kRoutePsOff = kRouteRows * kRouteLdz * 4;
 constexpr int kRouteCntOff = kRoutePsOff + 8 * kRouteMaxE * 4;
 static_assert(kRouteCntOff + 2 * kRouteMaxE * 4 <= 160 * 1024, "router tile and statistics fit LDS");
 
-// ---------------------------------------------------------------------------------------------
-// low-level helpers
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void glds16(const void* gptr, unsigned lds_addr) {
-    // 64 lanes x 16 bytes -> LDS[lds_addr + 16*lane]; lds_addr must be wave-uniform.
-    const unsigned base = __builtin_amdgcn_readfirstlane(lds_addr);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
-                 : "v"(gptr), "s"(base)
-                 : "memory", "m0");
-}
 
-__device__ __forceinline__ void glds16_s(const void* sbase, unsigned voff, unsigned lds_addr) {
-    // as glds16, the source address given as a wave-uniform base plus a 32-bit byte offset per lane
-    const unsigned base = __builtin_amdgcn_readfirstlane(lds_addr);
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(voff), "s"(sbase), "s"(base)
-                 : "memory", "m0");
-}
-
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    // gfx9 encoding: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14; other counters untouched
-    static_assert(N >= 0 && N < 64, "vmcnt range");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
-}
-
-// Workgroup barrier that orders LDS traffic only: earlier LDS operations of the wavefront are
-// complete, outstanding global stores and loads are left in flight (__syncthreads() would wait for
-// every global store the compiler knows of, i.e. for the whole epilogue of a tile to reach memory).
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
-    return (unsigned)(size_t)(__attribute__((address_space(3))) const char*)p;
-}
-
-__device__ __forceinline__ bf16x8 lds_read16(const char* p) {
-    return *reinterpret_cast<const bf16x8*>(p);
-}
-
-__device__ __forceinline__ bf16x8 lds_read_tr8(const char* p0, const char* p1) {
-    typedef __attribute__((address_space(3))) short4v* lp;
-    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p0);
-    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p1);
-    union { short4v s[2]; bf16x8 v; } u;
-    u.s[0] = lo;
-    u.s[1] = hi;
-    return u.v;
-}
-
-// K-contiguous tile: rows of BK elements, CPR = BK/8 chunks per row.
-template <int BK> struct KTile {
-    static constexpr int CPR = BK / 8;
-    static constexpr int RP = 256 / (BK * 2);   // rows per 256 bytes
-    __device__ static __forceinline__ int swz(int row) { return (row / RP) & (CPR - 1); }
-    // byte offset of logical chunk cc of row
-    __device__ static __forceinline__ int off(int row, int cc) {
-        return (row * CPR + (cc ^ swz(row))) * 16;
-    }
-};
-
-// N-contiguous tile: BK rows of BC elements, CPR = BC/8 chunks per row (>= 16), read for
-// v_mfma_f32_16x16x32_bf16: a fragment is 16 columns x 32 reduction
-// indices; lane l ends with column l%16 and indices 8*(l/16) .. +7.  Two transposing reads (K rows
-// krow and krow+4) of the 4 x 16 block that a group of 16 lanes addresses.  The swizzle keeps the four
-// K rows of a group and the groups 8 rows apart in different banks.
-template <int BC> struct NTile16 {
-    static constexpr int CPR = BC / 8;
-    __device__ static __forceinline__ int swz(int krow) { return ((krow & 3) << 2) | (((krow >> 3) & 1) << 1); }
-    __device__ static __forceinline__ int off(int krow, int col) {
-        return (krow * CPR + ((col >> 3) ^ swz(krow))) * 16 + (col & 7) * 2;
-    }
-    // byte offset of the first read of the fragment at columns col0 .. col0+15, reduction indices 0..31;
-    // the second read is 4 K rows (4 * CPR * 16 bytes) further on
-    __device__ static __forceinline__ int frag_off(int col0, int lane) {
-        return off(8 * (lane >> 4) + ((lane & 15) >> 2), col0 + 4 * (lane & 3));
-    }
-};
-
-// four floats to four bfloat16 (round to nearest even); converting pairs as vectors lets the compiler
-// use one packed conversion per pair instead of a conversion, a shift and an OR per value
-__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
-    typedef __attribute__((ext_vector_type(2))) float f32x2v;
-    typedef __attribute__((ext_vector_type(2))) bf16 bf16x2v;
-    union { bf16x2v h[2]; uint2 u; } p;
-    p.h[0] = __builtin_convertvector(f32x2v{a, b}, bf16x2v);
-    p.h[1] = __builtin_convertvector(f32x2v{c, d}, bf16x2v);
-    return p.u;
-}
-
-// ---------------------------------------------------------------------------------------------
-// tile table: [0] = number of entries; entry i at kTileBase + 4i: expert, first row, rows in tile
-// (0 for the entry that pads an expert to an even number of places)
-// ---------------------------------------------------------------------------------------------
-constexpr int kTileBase = 64;
-constexpr int kMaxTableExperts = 512;   // build_tiles_kernel: one thread per expert
-constexpr int kPairSpins = 48;      // polls of the partner's arrival, roughly a microsecond apart
-constexpr int kPairCap = 2048;      // meeting counters behind the tile table
-constexpr int kPairMinK = 4096;     // tiles this long are worth the meeting (its cost: a few microseconds)
 
 __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restrict__ offsets, int E,
-                                                          int total_rows, int BM,
+                                                          int total_rows, int BM, int pad_even,
                                                           int32_t* __restrict__ meta, int32_t* __restrict__ pair_cnt) {
     if (pair_cnt != nullptr)
         for (int i = threadIdx.x; i < kPairCap; i += 512) pair_cnt[i] = 0;
@@ -233,7 +86,7 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
     // Every expert takes an even number of places in the list (the odd one out is an entry without
     // rows, which the workgroups skip): the kernels hand out the list in pairs of row tiles that run
     // side by side and share the weight tile through L2, and a pair must not straddle two experts.
-    const int ns = (nt + 1) & ~1;
+    const int ns = pad_even ? (nt + 1) & ~1 : nt;
     lrows[t] = r1 - r0;
     __syncthreads();
     // Order of the experts in the tile list.  The persistent workgroups walk the list in a fixed
@@ -306,26 +159,7 @@ __global__ __launch_bounds__(512) void build_tiles_kernel(const int32_t* __restr
 // straight-line code and absent rows have no MFMAs.
 // The products are v_mfma_f32_16x16x32_bf16 (at the card's power limit this form sustains about a
 // sixth more than 32x32x16): a strip is two 16-row halves, the 64 columns four 16-column blocks.
-constexpr int kXwWaves = 8;
-constexpr int kXwThreads = kXwWaves * 64;
 
-struct TileRef {
-    int valid, expert, row0, rows, nt;
-    int pair;       // index of the meeting counter shared with the partner tile, or -1
-};
-
-// Wavefronts that share one staging region of 32 KiB in the epilogue, per epilogue kind: the staging
-// areas live in the operand buffers the last stage has released.  Kinds whose eight areas fit two
-// regions leave a third buffer free, which then takes the next tile's W(1) ahead of time.
-template <int EPI> struct Staging {
-    static constexpr int SC = EPI == EPI_SWIGLU_FWD ? 96 : 64;   // columns per staging row
-    static constexpr int SROW = SC * 2 + 16;                    // row stride in bytes
-    static constexpr int WSTG = (EPI == EPI_SWIGLU_BWD ? 2 : 1) * 32 * SROW;   // bytes per wavefront
-    static constexpr int RW = 32768 / WSTG < kXwWaves ? 32768 / WSTG : kXwWaves;
-    static constexpr int REGIONS = (EPI == EPI_F32 || EPI == EPI_ROUTE) ? 0 : (kXwWaves + RW - 1) / RW;
-    static constexpr bool PREW1 = REGIONS <= 2;
-    static_assert(REGIONS <= 3, "three operand buffers are free in the epilogue");
-};
 
 // pre: what the previous tile has already requested for this one (bit 0: X(0) and W(0), bit 1: W(1));
 // g0: number of K stages this workgroup has run before this tile (the LDS buffers rotate on).
@@ -701,8 +535,6 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
             }
     } else {
         using SG = Staging<EPI>;
-        constexpr int SROW = SG::SROW;                  // staging row stride in bytes
-        constexpr int CPRS = SG::SC / 8;                // 16-byte chunks per staging row
         // Staging area of this wavefront: region 0 is the X buffer of the last stage, region 1 its W
         // buffer, region 2 (SwiGLU backward only) the W buffer that would otherwise hold W(1) of the
         // next tile.
@@ -710,162 +542,10 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
         const int rbase = region == 0 ? xbuf(nk - 1) * XBYTES
                                       : WBASE + (region == 1 ? wbuf(nk - 1) : wbuf(nk + 1)) * WBYTES;
         char* stg = smem + rbase + (wave % SG::RW) * SG::WSTG;
-        // SWIGLU_BWD stages the saved activations A and B of a strip in two areas of 32 x 64 values:
-        // they are fetched as whole 128-byte row segments (one request per cache line instead of one
-        // per 16 bytes in the accumulator layout), a strip ahead, picked up from LDS in the
-        // accumulator layout, and replaced in place by dA and dB, which leave as row segments again.
-        [[maybe_unused]] char* stgb = stg + 32 * SROW;
-        [[maybe_unused]] uint4 av0, av1, av2, av3, bv0, bv1, bv2, bv3;
-        // the 64 columns of a wavefront are inside N or outside as a whole (N is a multiple of 64)
-        [[maybe_unused]] const bool cols_ok = n0 + wn * 64 < g.N;
-#define UNIPOOL_LOAD_AB1(TMX, IT)                                                                  \
-    {                                                                                              \
-        const int r_ = min((wm + 2 * (TMX)) * 32 + (IT) * 8 + (lane >> 3), rows - 1);              \
-        const size_t o_ = (size_t)(row0 + r_) * g.N + n0 + wn * 64 + (lane & 7) * 8;               \
-        av##IT = *reinterpret_cast<const uint4*>(g.aux_a + o_);                                    \
-        bv##IT = *reinterpret_cast<const uint4*>(g.aux_b + o_);                                    \
-    }
-#define UNIPOOL_LOAD_AB(TMX)                                                                       \
-    UNIPOOL_LOAD_AB1(TMX, 0) UNIPOOL_LOAD_AB1(TMX, 1) UNIPOOL_LOAD_AB1(TMX, 2) UNIPOOL_LOAD_AB1(TMX, 3)
-        if constexpr (EPI == EPI_SWIGLU_BWD && MTV > 0) {
-            if (cols_ok) { UNIPOOL_LOAD_AB(0) }
-        }
-        // EPI_STORE adding to the destination: the old values of all strips are requested up front,
-        // in the layout the row segments leave in, so that their latency is paid once per tile.
-        [[maybe_unused]] uint4 oldv[MTV > 0 ? MTV : 1][4];
-        if constexpr (EPI == EPI_STORE) {
-            if (g.add) {
-#pragma unroll
-                for (int tm = 0; tm < MTV; tm++)
-#pragma unroll
-                    for (int it = 0; it < 4; it++) {
-                        const int id = it * 64 + lane;
-                        const int rr = min((wm + 2 * tm) * 32 + id / CPRS, rows - 1);
-                        const int col = min(n0 + wn * 64 + (id % CPRS) * 8, g.N - 8);
-                        oldv[tm][it] = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16*>(g.out0) +
-                                                                       (size_t)(row0 + rr) * g.ldo + col);
-                    }
-            }
-        }
-#pragma unroll
-        for (int tm = 0; tm < MTV; tm++) {
-            const int strip0 = (wm + 2 * tm) * 32;     // first row of the strip inside the tile
-            // -- registers -> staging rows
-            if constexpr (EPI == EPI_STORE) {
-#pragma unroll
-                for (int mh = 0; mh < (LH && tm == MTV - 1 ? 1 : 2); mh++)
-#pragma unroll
-                    for (int nb = 0; nb < 4; nb++) {
-                        const int c = 16 * nb + 4 * lg;
-                        *reinterpret_cast<uint2*>(stg + (16 * mh + l16) * SROW + c * 2) =
-                            pack4(acc[tm][mh][nb][0], acc[tm][mh][nb][1], acc[tm][mh][nb][2], acc[tm][mh][nb][3]);
-                    }
-            } else if constexpr (EPI == EPI_SWIGLU_FWD) {
-#pragma unroll
-                for (int q = 0; q < (LH && tm == MTV - 1 ? 2 : 4); q++) {
-                    const int mh = q >> 1, nbg = q & 1;       // blocks nbg and 2 + nbg: gate and up of the same columns
-                    const int c = 16 * nbg + 4 * lg;
-                    char* srow = stg + (16 * mh + l16) * SROW;
-                    float a[4], b[4], h[4];
-#pragma unroll
-                    for (int i = 0; i < 4; i++) {
-                        a[i] = acc[tm][mh][nbg][i];
-                        b[i] = acc[tm][mh][2 + nbg][i];
-                        h[i] = silu_f(a[i]) * b[i];
-                    }
-                    *reinterpret_cast<uint2*>(srow + c * 2) = pack4(a[0], a[1], a[2], a[3]);
-                    *reinterpret_cast<uint2*>(srow + (32 + c) * 2) = pack4(b[0], b[1], b[2], b[3]);
-                    *reinterpret_cast<uint2*>(srow + (64 + c) * 2) = pack4(h[0], h[1], h[2], h[3]);
-                }
-            } else {   // EPI_SWIGLU_BWD
-                if (cols_ok) {
-                    const int so = (lane >> 3) * SROW + (lane & 7) * 16;
-                    *reinterpret_cast<uint4*>(stg + so) = av0;
-                    *reinterpret_cast<uint4*>(stgb + so) = bv0;
-                    *reinterpret_cast<uint4*>(stg + so + 8 * SROW) = av1;
-                    *reinterpret_cast<uint4*>(stgb + so + 8 * SROW) = bv1;
-                    *reinterpret_cast<uint4*>(stg + so + 16 * SROW) = av2;
-                    *reinterpret_cast<uint4*>(stgb + so + 16 * SROW) = bv2;
-                    *reinterpret_cast<uint4*>(stg + so + 24 * SROW) = av3;
-                    *reinterpret_cast<uint4*>(stgb + so + 24 * SROW) = bv3;
-                    if (tm + 1 < MTV) { UNIPOOL_LOAD_AB(tm + 1) }
-                }
-#pragma unroll
-                for (int mh = 0; mh < (LH && tm == MTV - 1 ? 1 : 2); mh++)
-#pragma unroll
-                    for (int nb = 0; nb < 4; nb++) {
-                        const int c = 16 * nb + 4 * lg;                 // column inside the wave's 64
-                        float da[4] = {0.f, 0.f, 0.f, 0.f}, db[4] = {0.f, 0.f, 0.f, 0.f};
-                        // a lane overwrites exactly the eight bytes of A and of B it has read
-                        uint2* pa = reinterpret_cast<uint2*>(stg + (16 * mh + l16) * SROW + c * 2);
-                        uint2* pb = reinterpret_cast<uint2*>(stgb + (16 * mh + l16) * SROW + c * 2);
-                        if (cols_ok) {
-                            union { uint2 u; bf16 h[4]; } a4, b4;
-                            a4.u = *pa;
-                            b4.u = *pb;
-#pragma unroll
-                            for (int i = 0; i < 4; i++) {
-                                const float a = (float)a4.h[i], b = (float)b4.h[i];
-                                const float dh = acc[tm][mh][nb][i];
-                                const float sg = logistic_f(a);
-                                da[i] = dh * b * sg * (1.0f + a * (1.0f - sg));
-                                db[i] = dh * a * sg;
-                            }
-                        }
-                        *pa = pack4(da[0], da[1], da[2], da[3]);
-                        *pb = pack4(db[0], db[1], db[2], db[3]);
-                    }
-            }
-            // -- staging rows -> global, 16 bytes per lane
-            constexpr int NCH = (EPI == EPI_SWIGLU_BWD ? 2 : 1) * CPRS;     // chunks per output row
-#pragma unroll
-            for (int it = 0; it < 32 * NCH / 64; it++) {
-                const int id = it * 64 + lane;
-                const int srow = id / NCH;
-                const int ch = id % NCH;
-                const int rr = strip0 + srow;
-                if (rr >= rows) continue;
-                const size_t grow = (size_t)(row0 + rr);
-                if constexpr (EPI == EPI_STORE) {
-                    const uint4 v = *reinterpret_cast<const uint4*>(stg + srow * SROW + ch * 16);
-                    const int col = n0 + wn * 64 + ch * 8;
-                    if (col < g.N) {
-                        bf16* dst = reinterpret_cast<bf16*>(g.out0) + grow * g.ldo + col;
-                        if (g.add) {
-                            union { uint4 u; bf16 h[8]; } o, n;
-                            o.u = oldv[tm][it];
-                            n.u = v;
-#pragma unroll
-                            for (int i = 0; i < 8; i++) n.h[i] = (bf16)((float)o.h[i] + (float)n.h[i]);
-                            *reinterpret_cast<uint4*>(dst) = n.u;
-                        } else {
-                            *reinterpret_cast<uint4*>(dst) = v;
-                        }
-                    }
-                } else if constexpr (EPI == EPI_SWIGLU_FWD) {
-                    const uint4 v = *reinterpret_cast<const uint4*>(stg + srow * SROW + ch * 16);
-                    const int which = ch >> 2;
-                    const int col = f0 + wn * 32 + (ch & 3) * 8;
-                    if (col < g.N) {
-                        bf16* base = reinterpret_cast<bf16*>(which == 0 ? g.out0 : (which == 1 ? g.out1 : g.out2));
-                        *reinterpret_cast<uint4*>(base + grow * g.ldo + col) = v;
-                    }
-                } else {
-                    const int which = ch >> 3;
-                    const uint4 v = *reinterpret_cast<const uint4*>((which ? stgb : stg) + srow * SROW + (ch & 7) * 16);
-                    const int col = n0 + wn * 64 + (ch & 7) * 8;
-                    if (col < g.N) {
-                        bf16* dst = reinterpret_cast<bf16*>(g.out0) + grow * g.ldo + which * g.N + col;
-                        *reinterpret_cast<uint4*>(dst) = v;
-                    }
-                }
-            }
-        }
+        xw_staged_epilogue<EPI, MTV, LH, true>(epi_args(g), AccArray<MTV>{acc}, stg, rows, row0, n0, f0, wm, 2, wn, lane);
     }
     PHASE_STAMP(t_end);
     PHASE_COMMIT(t_begin, t_filled, t_looped, t_end);
-#undef UNIPOOL_LOAD_AB
-#undef UNIPOOL_LOAD_AB1
 }
 
 // Second half of EPI_ROUTE, run by all wavefronts once the tile's logits are in LDS: logits to
@@ -1440,17 +1120,6 @@ constexpr int kPtqBK = 32, kPtqNS = 4, kPtqWaves = 8;       // gemm_ptq
 constexpr int kGemmLds = kNS * kBM * kBK * 2 + (kNS + 1) * kBN * kBK * 2;   // 2 X stages + 3 W stages = 160 KiB
 constexpr int kPtqLds = kPtqNS * 2 * kPtqBK * 256 * 2;            // 128 KiB
 
-int num_cus() {
-    static int n = 0;
-    if (n == 0) {
-        int dev = 0;
-        hipDeviceProp_t p;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess)
-            n = p.multiProcessorCount;
-        if (n <= 0) n = 256;
-    }
-    return n;
-}
 
 template <bool WK, int EPI, bool KTAIL = false>
 hipError_t run_xw(GemmArgs a, int max_row_tiles, hipStream_t st) {
@@ -1489,13 +1158,39 @@ int32_t* pair_counters(int32_t* meta, int E, int total_rows) {
     return meta + kTileBase + 4 * (total_rows / kBM + 2 * E);
 }
 
+// Timing aid of debugging builds: UNIPOOL_W0=1 makes every expert read the weights of expert 0, so that the
+// weight stream comes from the caches instead of HBM (same instructions, results meaningless).
+long long debug_w_stride(long long w_stride) {
+#ifdef UNIPOOL_DEBUG_SWITCHES
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("UNIPOOL_W0");
+        v = (e && e[0] == '1') ? 1 : 0;
+    }
+    return v == 1 ? 0 : w_stride;
+#else
+    return w_stride;
+#endif
+}
+
 hipError_t build_tiles(const int32_t* offsets, int E, int total_rows, int32_t* meta, hipStream_t st) {
-    build_tiles_kernel<<<1, 512, 0, st>>>(offsets, E, total_rows, kBM, meta, pair_counters(meta, E, total_rows));
+    build_tiles_kernel<<<1, 512, 0, st>>>(offsets, E, total_rows, kBM, 1, meta, pair_counters(meta, E, total_rows));
     return hipGetLastError();
 }
 
 }  // namespace
 
+int num_cus() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t p;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess)
+            n = p.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
 
 bool mfma_ffn_supported(const unipool_shape& s) {
     // the tile table is built by one workgroup with a thread per expert; the weight-gradient kernel
@@ -1546,7 +1241,7 @@ hipError_t mfma_ffn_gate_up(const unipool_shape& s, const void* x_perm, const in
     if (e != hipSuccess) return e;
     GemmArgs a = {};
     a.X = (const bf16*)x_perm; a.ldx = d;
-    a.W = (const bf16*)wgu; a.w_stride = 2LL * f * d; a.ldw = d;
+    a.W = (const bf16*)wgu; a.w_stride = debug_w_stride(2LL * f * d); a.ldw = d;
     a.K = d; a.N = f; a.n_tiles_n = cdiv(f, kBN / 2);
     a.tile_meta = tile_meta; a.out0 = a_out; a.out1 = b_out; a.out2 = h_out; a.ldo = f;
     a.up_rows = f;
@@ -1562,7 +1257,7 @@ hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_
     if (e != hipSuccess) return e;
     GemmArgs b = {};
     b.X = (const bf16*)h_out; b.ldx = f;
-    b.W = (const bf16*)wd; b.w_stride = (long long)d * f; b.ldw = f;
+    b.W = (const bf16*)wd; b.w_stride = debug_w_stride((long long)d * f); b.ldw = f;
     b.K = f; b.N = d; b.n_tiles_n = cdiv(d, kBN);
     b.tile_meta = tile_meta; b.launch_slot = 1; b.out0 = y; b.ldo = d;
     if (b.K >= kPairMinK) { b.pair_cnt = pair_counters(tile_meta, s.E, S); b.pair_cap = kPairCap; }
@@ -1578,7 +1273,7 @@ hipError_t mfma_ffn_dgrad(const unipool_shape& s, const void* dy, const void* a_
     if (e != hipSuccess) return e;
     GemmArgs a = {};   // dH = dY W_down (W_down[e] is [d][f]: reduction index strided), then SwiGLU backward
     a.X = (const bf16*)dy; a.ldx = d;
-    a.W = (const bf16*)wd; a.w_stride = (long long)d * f; a.ldw = f;
+    a.W = (const bf16*)wd; a.w_stride = debug_w_stride((long long)d * f); a.ldw = f;
     a.K = d; a.N = f; a.n_tiles_n = cdiv(f, kBN);
     a.tile_meta = tile_meta; a.out0 = d_act; a.ldo = 2 * f;
     a.aux_a = (const bf16*)a_in; a.aux_b = (const bf16*)b_in;
@@ -1586,7 +1281,7 @@ hipError_t mfma_ffn_dgrad(const unipool_shape& s, const void* dy, const void* a_
     if (e != hipSuccess) return e;
     GemmArgs b = {};   // dX = [dA|dB] W_gate_up (W_gate_up[e] is [2f][d])
     b.X = (const bf16*)d_act; b.ldx = 2 * f;
-    b.W = (const bf16*)wgu; b.w_stride = 2LL * f * d; b.ldw = d;
+    b.W = (const bf16*)wgu; b.w_stride = debug_w_stride(2LL * f * d); b.ldw = d;
     b.K = 2 * f; b.N = d; b.n_tiles_n = cdiv(d, kBN);
     b.tile_meta = tile_meta; b.launch_slot = 1; b.out0 = dx; b.ldo = d;
     if (b.K >= kPairMinK) { b.pair_cnt = pair_counters(tile_meta, s.E, S); b.pair_cap = kPairCap; }
