@@ -24,7 +24,9 @@ Pins (tests/test_oracle_*.py): dense brute force of Eq. 2 with Python loops,
 full-sort top-k, permutation invariants, NormRouter closed forms, pool-loss
 closed forms (uniform usage, single expert, L = 1 reducing to Eq. 3, Eq. 6
 identity), central finite differences for every gradient, E = 1 reducing to a
-dense SwiGLU MLP; the one-step-behind loop against a hand count of the previous
+dense SwiGLU MLP; the softmax router (comparison rows of Sec. 5.4) by rows summing to one, the
+pool loss equal to alpha under exactly uniform usage, shift invariance and finite differences;
+the one-step-behind loop against a hand count of the previous
 micro-batch's slots and finite differences of the lagged objective; the
 recompute half against the forward record.  `c_from_samples` (App. G, Alg. 1) is pinned by
 loops on small draws and closed cases, `estimate_c` statistically; `distinct_experts`
@@ -53,6 +55,26 @@ def norm_router_scores(z, sigma, c, eps):
     return sigma * c * np.maximum(0.0, zhat), n
 
 
+def softmax_router_scores(z):
+    """The softmax router of the comparison rows (Sec. 3, Eq. 1 and Eq. 3; Sec. 5.4 ablation
+    "softmax router"): p_i = exp(z_i) / sum_j exp(z_j).  The gate of a selected expert is
+    its probability p_i (no renormalisation over the top-k: with the paper's top-1 routing a
+    renormalised gate would be the constant 1 and the router would get no gradient from
+    the layer output), and the auxiliary losses use p as the routing probability."""
+    z = np.asarray(z, F64)
+    e = np.exp(z - np.max(z, axis=-1, keepdims=True))
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def router_scores(z, sigma, c, eps, router="norm"):
+    """Scores of the router kind: "norm" is Eq. 7, "softmax" the softmax router."""
+    if router == "norm":
+        return norm_router_scores(z, sigma, c, eps)
+    assert router == "softmax", router
+    z = np.asarray(z, F64)
+    return softmax_router_scores(z), np.sqrt(np.sum(z * z, axis=-1))
+
+
 def topk_select(z, k):
     """Indices of the k largest logits per token, descending, ties -> lower index."""
     z = np.asarray(z, F64)
@@ -60,14 +82,14 @@ def topk_select(z, k):
     return order[..., :k].astype(np.int32)
 
 
-def route(x, w_router, k, sigma, c, eps, idx=None):
+def route(x, w_router, k, sigma, c, eps, idx=None, router="norm"):
     """Router of one layer: logits, scores, top-k, gates and the layer statistics
     the auxiliary losses need (Sec. 4.2: token counts per expert and the sum of
     routing scores per expert over the tokens of the layer).
     `idx` replaces the selection (used by tests to impose the other, equally
     valid choice on tokens whose logits tie within rounding)."""
     z = router_logits(x, w_router)
-    s, n = norm_router_scores(z, sigma, c, eps)
+    s, n = router_scores(z, sigma, c, eps, router)
     idx = topk_select(z, k) if idx is None else np.asarray(idx, dtype=np.int32)
     gate = np.take_along_axis(s, idx.astype(np.int64), axis=1)
     E = z.shape[1]
@@ -178,10 +200,10 @@ def combine(y_perm, row_of_slot, gate=None):
     return out
 
 
-def moe_layer_fwd(x, w_router, w_gate, w_up, w_down, k, sigma, c, eps, idx=None):
+def moe_layer_fwd(x, w_router, w_gate, w_up, w_down, k, sigma, c, eps, idx=None, router="norm"):
     """Eq. 2 for one layer, through routing, dispatch, experts and combine."""
     E = w_gate.shape[0]
-    r = route(x, w_router, k, sigma, c, eps, idx)
+    r = route(x, w_router, k, sigma, c, eps, idx, router)
     offsets, row_of_slot, slot_of_row = permutation(r["idx"], E)
     x_perm = permute_rows(np.asarray(x, F64), slot_of_row, k)
     a, b, h, y = expert_ffn_fwd(x_perm, offsets, w_gate, w_up, w_down)
@@ -275,14 +297,15 @@ def expert_ffn_bwd(dy_perm, x_perm, a, b, offsets, w_gate, w_up, w_down):
     return dx, dwg, dwu, dwd, da, db
 
 
-def route_bwd(x, w_router, z, idx, dgate, aux_coef, sigma, c, eps):
-    """Backward of Eq. 7 and of z = W h.
+def route_bwd(x, w_router, z, idx, dgate, aux_coef, sigma, c, eps, router="norm"):
+    """Backward of Eq. 7 (or of the softmax router) and of z = W h.
 
     ds_{t,i} = aux_coef_i (every expert; zero if aux_coef is None)
                + dgate_{t,j} where i = idx_{t,j};
     d sigma = sum ds * c * relu(zhat);  dzhat = ds * sigma c [zhat > 0];
     dz_j = dzhat_j/(n+eps) - z_j <dzhat, z> / (n (n+eps)^2);
     dW = dz^T x;  dx = dz W.
+    router = "softmax":  dz_j = p_j (ds_j - <ds, p>)  (Jacobian of the softmax), d sigma = 0.
     Returns (dx[T,d], dw_router[E,d], dsigma, dz[T,E])."""
     x = np.asarray(x, F64)
     w_router = np.asarray(w_router, F64)
@@ -294,6 +317,11 @@ def route_bwd(x, w_router, z, idx, dgate, aux_coef, sigma, c, eps):
     dgate = np.asarray(dgate, F64)
     for j in range(idx.shape[1]):
         ds[np.arange(T), idx[:, j]] += dgate[:, j]
+    if router == "softmax":
+        p = softmax_router_scores(z)
+        dz = p * (ds - np.sum(ds * p, axis=1, keepdims=True))
+        return dz @ w_router, dz.T @ x, 0.0, dz
+    assert router == "norm", router
     n = np.sqrt(np.sum(z * z, axis=1))
     zhat = z / (n + eps)[:, None]
     pos = zhat > 0.0
@@ -308,14 +336,14 @@ def route_bwd(x, w_router, z, idx, dgate, aux_coef, sigma, c, eps):
     return dx, dw, dsigma, dz
 
 
-def moe_layer_bwd(fw, x, w_router, w_gate, w_up, w_down, dout, aux_coef, k, sigma, c, eps):
+def moe_layer_bwd(fw, x, w_router, w_gate, w_up, w_down, dout, aux_coef, k, sigma, c, eps, router="norm"):
     """Backward of one layer given its forward record `fw` (from moe_layer_fwd)."""
     dy, dgate = combine_bwd(dout, fw["y_perm"], fw["row_of_slot"], fw["gate"])
     dxp, dwg, dwu, dwd, da, db = expert_ffn_bwd(dy, fw["x_perm"], fw["a"], fw["b"], fw["offsets"],
                                                 w_gate, w_up, w_down)
     dx_experts = combine(dxp, fw["row_of_slot"], None)       # sum over the k copies
     dx_router, dwr, dsigma, dz = route_bwd(x, w_router, fw["z"], fw["idx"], dgate, aux_coef,
-                                           sigma, c, eps)
+                                           sigma, c, eps, router)
     return dict(dy_perm=dy, dgate=dgate, dx_perm=dxp, da=da, db=db, dw_gate=dwg, dw_up=dwu,
                 dw_down=dwd, dx_experts=dx_experts, dx_router=dx_router,
                 dx=dx_experts + dx_router, dw_router=dwr, dsigma=dsigma, dz=dz)
@@ -325,7 +353,7 @@ def moe_layer_bwd(fw, x, w_router, w_gate, w_up, w_down, dout, aux_coef, k, sigm
 # Whole step over the L layers that share the pool
 # ---------------------------------------------------------------------------
 def pool_step(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps, alpha,
-              fbar_in=None, idxs=None, aux="pool"):
+              fbar_in=None, idxs=None, aux="pool", router="norm"):
     """Forward of all layers, auxiliary loss, backward of all layers.
     Expert weight gradients are summed over the layers (one shared pool).
 
@@ -337,7 +365,7 @@ def pool_step(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps,
     L = len(xs)
     T = xs[0].shape[0]
     fws = [moe_layer_fwd(xs[l], w_routers[l], w_gate, w_up, w_down, k, sigmas[l], c, eps,
-                         None if idxs is None else idxs[l])
+                         None if idxs is None else idxs[l], router)
            for l in range(L)]
     counts = np.stack([fw["counts"] for fw in fws])
     psum = np.stack([fw["psum"] for fw in fws])
@@ -360,7 +388,7 @@ def pool_step(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps,
     bws = []
     for l in range(L):
         bw = moe_layer_bwd(fws[l], xs[l], w_routers[l], w_gate, w_up, w_down, grad_outs[l], coefs[l],
-                           k, sigmas[l], c, eps)
+                           k, sigmas[l], c, eps, router)
         dwg += bw["dw_gate"]
         dwu += bw["dw_up"]
         dwd += bw["dw_down"]
@@ -397,12 +425,12 @@ def micro_batch_loop(batches, w_routers, w_gate, w_up, w_down, k, sigmas, c, eps
     return results
 
 
-def objective(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps, alpha, fbar):
+def objective(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps, alpha, fbar, router="norm"):
     """Lambda = sum_l <Out^(l), G^(l)> + L_pool with fbar held constant (App. F)."""
     total = 0.0
     psum = []
     for l in range(len(xs)):
-        fw = moe_layer_fwd(xs[l], w_routers[l], w_gate, w_up, w_down, k, sigmas[l], c, eps)
+        fw = moe_layer_fwd(xs[l], w_routers[l], w_gate, w_up, w_down, k, sigmas[l], c, eps, None, router)
         total += float(np.sum(fw["out"] * np.asarray(grad_outs[l], F64)))
         psum.append(fw["psum"])
     psum = np.stack(psum)
