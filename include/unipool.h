@@ -52,6 +52,13 @@ extern "C" {
 #define UNIPOOL_F32  0
 #define UNIPOOL_BF16 1
 
+/* Router kinds.  NORM is the paper's NormRouter (Sec. 4.3, Eq. 7).  SOFTMAX is the router of the comparison
+ * rows (Sec. 3, Eq. 1 and Eq. 3; ablation "softmax router" of Sec. 5.4): score p_i = exp(z_i) / sum_j exp(z_j),
+ * selection of the k largest logits as for NORM, gate = p of the selected expert (no renormalisation over the
+ * top-k), and the auxiliary losses take p as the routing probability.  sigma, c and eps are not used. */
+#define UNIPOOL_ROUTER_NORM    0
+#define UNIPOOL_ROUTER_SOFTMAX 1
+
 typedef struct unipool_shape {
     int32_t T;          /* tokens in this layer call */
     int32_t d_model;    /* d */
@@ -64,6 +71,7 @@ typedef struct unipool_shape {
     float c;            /* NormRouter calibration constant (App. G); a plain input */
     float eps;          /* NormRouter epsilon, added outside the norm (Eq. 7) */
     float alpha_pool;   /* pool auxiliary loss coefficient (Eq. 5) */
+    int32_t router;     /* UNIPOOL_ROUTER_NORM or UNIPOOL_ROUTER_SOFTMAX (unipool_route, unipool_route_bwd) */
 } unipool_shape;
 
 /* Bytes of workspace that is enough for every entry point at this shape. */
@@ -82,6 +90,7 @@ int unipool_version(void);
  *   exact ties to the lower index;  topk_gate[t, j] = s_{t, topk_idx[t,j]} (raw score).
  *   counts[i] = number of (t, j) with topk_idx[t,j] == i;  psum[i] = sum_t s_{t,i} over
  *   ALL experts (the statistics f and P of Sec. 4.2 before normalisation).
+ *   With shape->router == UNIPOOL_ROUTER_SOFTMAX the score is s_i = softmax(z)_i instead.
  * in : x [T, d] act;  w_router [E, d] act
  * out: topk_idx [T, k] int32;  topk_gate [T, k] float;  logits [T, E] float (saved
  *      for the backward pass; may be NULL);  counts [E] int32;  psum [E] float.
@@ -99,6 +108,8 @@ int unipool_route(const unipool_shape* shape, const void* x, const void* w_route
  *   d_sigma  = sum_{t,i} ds_{t,i} c max(0, zhat_{t,i});  dzhat = ds sigma c [zhat > 0]
  *   dz_j     = dzhat_j/(n+eps) - z_j <dzhat, z> / (n (n+eps)^2)
  *   d_w_router = dz^T x;   dx += dz W  (dx_accumulate != 0) or dx = dz W.
+ *   UNIPOOL_ROUTER_SOFTMAX:  dz_j = p_j (ds_j - <ds, p>),  d_sigma = 0.
+ *   In bfloat16 mode dz is rounded to bfloat16 before the two products.
  * in : x, w_router as in unipool_route;  logits [T, E] float from unipool_route;
  *      topk_idx [T, k];  dgate [T, k] float;  aux_coef [E] float or NULL.
  * out: d_w_router [E, d] float (overwritten);  d_sigma [1] float (overwritten);

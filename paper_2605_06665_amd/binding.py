@@ -9,6 +9,8 @@ from typing import Optional, Sequence
 
 F32 = 0
 BF16 = 1
+ROUTER_NORM = 0
+ROUTER_SOFTMAX = 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -23,7 +25,7 @@ class Shape(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32),
                 ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("L", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("sigma", ctypes.c_float), ("c", ctypes.c_float),
-                ("eps", ctypes.c_float), ("alpha_pool", ctypes.c_float)]
+                ("eps", ctypes.c_float), ("alpha_pool", ctypes.c_float), ("router", ctypes.c_int32)]
 
 
 ENTRY_POINTS = ("unipool_workspace_bytes", "unipool_last_error", "unipool_version", "unipool_route",

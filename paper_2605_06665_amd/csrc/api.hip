@@ -115,6 +115,9 @@ int validate_shape(const unipool_shape* s, const char* fn) {
     if (s->dtype == UNIPOOL_BF16 && (s->d_model % 64 != 0 || s->d_ff % 64 != 0))
         return set_error(UNIPOOL_EINVAL, "%s: bfloat16 mode needs d_model and d_ff to be multiples of 64 (d=%d f=%d)",
                          fn, s->d_model, s->d_ff);
+    if (s->router != UNIPOOL_ROUTER_NORM && s->router != UNIPOOL_ROUTER_SOFTMAX)
+        return set_error(UNIPOOL_EINVAL, "%s: router %d is neither UNIPOOL_ROUTER_NORM nor UNIPOOL_ROUTER_SOFTMAX", fn,
+                         s->router);
     if (!(s->sigma > 0.f)) return set_error(UNIPOOL_EINVAL, "%s: sigma must be positive", fn);
     if (!(s->eps >= 0.f)) return set_error(UNIPOOL_EINVAL, "%s: eps must be non-negative", fn);
     return UNIPOOL_OK;

@@ -36,6 +36,7 @@ struct GemmArgs {
     float* psum_part;
     int topk;
     float sigma_c, eps;
+    int softmax;          // EPI_ROUTE: softmax router instead of the NormRouter
     // Meeting point of the two workgroups that run the two row tiles of an expert side by side (one
     // zeroed counter per pair of list positions, or null): they start their tiles together, so the
     // weight tile one of them fetches is still in L2 when the other asks for it.

@@ -582,7 +582,7 @@ __device__ __forceinline__ void route_epilogue(const GemmArgs& g, char* smem, co
             const int e = sl + GS * i;
             z[i] = (e < E) ? zr[e] : 0.f;
         }
-        route_select<GS, VPL>(z, sl, E, g.topk, g.sigma_c, g.eps, lr < rows, (size_t)(row0 + lr), g.topk_idx,
+        route_select<GS, VPL>(z, sl, E, g.topk, g.sigma_c, g.eps, g.softmax != 0, lr < rows, (size_t)(row0 + lr), g.topk_idx,
                               g.topk_gate, lds_cnt + (wave >> 2) * kRouteMaxE, ps);
     }
 #pragma unroll
@@ -1228,7 +1228,7 @@ hipError_t mfma_route_fused(const unipool_shape& s, const void* x, const void* w
     a.out0 = z; a.ldo = s.E;
     a.flat_rows = s.T; a.flat_bm = kFlatBM;
     a.topk_idx = topk_idx; a.topk_gate = topk_gate; a.cnt_part = cnt_part; a.psum_part = psum_part;
-    a.topk = s.k; a.sigma_c = s.sigma * s.c; a.eps = s.eps;
+    a.topk = s.k; a.sigma_c = s.sigma * s.c; a.eps = s.eps; a.softmax = s.router == UNIPOOL_ROUTER_SOFTMAX;
     return run_xw<true, EPI_ROUTE>(a, cdiv(s.T, kBM), st);
 }
 

@@ -17,7 +17,7 @@ constexpr int kTokPerWave = kRouterTokensPerBlock / kWavesPerBlock;
 // final reduction over blocks is deterministic.
 template <int GS, int VPL>
 __global__ __launch_bounds__(256) void route_score_topk_kernel(
-    const float* __restrict__ logits, int T, int E, int k, float sigma_c, float eps,
+    const float* __restrict__ logits, int T, int E, int k, float sigma_c, float eps, int softmax,
     int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate,
     int32_t* __restrict__ cnt_part, float* __restrict__ psum_part) {
     constexpr int TPW = 64 / GS;                       // tokens per wavefront at a time
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void route_score_topk_kernel(
 #pragma unroll
         for (int i = 0; i < VPL; i++) z[i] = zn[i];
         if (tt + TPW < kTokPerWave) fetch(t + TPW, zn);          // the next token's logits, a round ahead
-        route_select<GS, VPL>(z, sl, E, k, sigma_c, eps, t < T, (size_t)t, topk_idx, topk_gate, lds_cnt, ps);
+        route_select<GS, VPL>(z, sl, E, k, sigma_c, eps, softmax != 0, t < T, (size_t)t, topk_idx, topk_gate, lds_cnt, ps);
     }
     // score sums: over the token groups of the wavefront (fixed order), then over the wavefronts
 #pragma unroll
@@ -106,7 +106,7 @@ template <typename TA, int GS, int VPL>
 __global__ __launch_bounds__(256) void route_bwd_dz_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ topk_idx,
     const float* __restrict__ dgate, const float* __restrict__ aux_coef, int T, int E, int k,
-    float sigma, float c, float eps, TA* __restrict__ dz, float* __restrict__ dsigma_part) {
+    float sigma, float c, float eps, int softmax, TA* __restrict__ dz, float* __restrict__ dsigma_part) {
     constexpr int TPW = 64 / GS;
     static_assert(kTokPerWave % TPW == 0, "whole rounds per wavefront");
     __shared__ float lds_ds[kWavesPerBlock];
@@ -143,6 +143,41 @@ __global__ __launch_bounds__(256) void route_bwd_dz_kernel(
 #pragma unroll
             for (int i = 0; i < VPL; i++)
                 if (sel == sl + GS * i) ds[i] += gd;
+        }
+        if (softmax) {
+            // dz_j = p_j (ds_j - <ds, p>) with p = softmax(z); sigma takes no part
+            float zmax = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < VPL; i++)
+                if (sl + GS * i < E) zmax = fmaxf(zmax, z[i]);
+#pragma unroll
+            for (int o = GS / 2; o > 0; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 64));
+            float pr[VPL];
+            float se = 0.f;
+#pragma unroll
+            for (int i = 0; i < VPL; i++) {
+                pr[i] = (sl + GS * i < E) ? expf(z[i] - zmax) : 0.f;
+                se += pr[i];
+            }
+#pragma unroll
+            for (int o = GS / 2; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
+            const float inv_se = 1.0f / se;
+            float dotp = 0.f;
+#pragma unroll
+            for (int i = 0; i < VPL; i++) {
+                pr[i] *= inv_se;
+                dotp += ds[i] * pr[i];
+            }
+#pragma unroll
+            for (int o = GS / 2; o > 0; o >>= 1) dotp += __shfl_xor(dotp, o, 64);
+            if (live) {
+#pragma unroll
+                for (int i = 0; i < VPL; i++) {
+                    const int e = sl + GS * i;
+                    if (e < E) dz[(size_t)t * E + e] = from_f32<TA>(pr[i] * (ds[i] - dotp));
+                }
+            }
+            continue;
         }
         const float n = sqrtf(ss);
         const float inv = 1.0f / (n + eps);
@@ -199,13 +234,13 @@ hipError_t launch_route_score_topk(const unipool_shape& s, const float* logits, 
     const int nblocks = cdiv(s.T, kRouterTokensPerBlock);
     // lanes per token and logits per lane by pool size
     if (s.E <= 128)
-        route_score_topk_kernel<16, 8><<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps,
+        route_score_topk_kernel<16, 8><<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps, s.router,
                                                                 topk_idx, topk_gate, cnt_part, psum_part);
     else if (s.E <= 256)
-        route_score_topk_kernel<16, 16><<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps,
+        route_score_topk_kernel<16, 16><<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps, s.router,
                                                                  topk_idx, topk_gate, cnt_part, psum_part);
     else
-        route_score_topk_kernel<32, 16><<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps,
+        route_score_topk_kernel<32, 16><<<nblocks, 256, 0, st>>>(logits, s.T, s.E, s.k, s.sigma * s.c, s.eps, s.router,
                                                                  topk_idx, topk_gate, cnt_part, psum_part);
     route_finalize_kernel<<<s.E, 256, 0, st>>>(cnt_part, psum_part, nblocks, s.E, counts, psum);
     return hipGetLastError();
@@ -224,7 +259,7 @@ hipError_t launch_route_bwd_dz(const unipool_shape& s, const float* logits, cons
     const int nblocks = cdiv(s.T, kRouterTokensPerBlock);
 #define UNIPOOL_DZ(TA, GS, VPL)                                                                        \
     route_bwd_dz_kernel<TA, GS, VPL><<<nblocks, 256, 0, st>>>(logits, topk_idx, dgate, aux_coef, s.T, s.E, \
-                                                              s.k, s.sigma, s.c, s.eps, (TA*)dz, dsigma_part)
+                                                              s.k, s.sigma, s.c, s.eps, s.router, (TA*)dz, dsigma_part)
     if (s.dtype == UNIPOOL_BF16) {
         if (s.E <= 128) UNIPOOL_DZ(bf16, 16, 8);
         else if (s.E <= 256) UNIPOOL_DZ(bf16, 16, 16);

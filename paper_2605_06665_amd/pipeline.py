@@ -51,13 +51,15 @@ class PoolStep:
               (Eq. 3) for every layer on its own, each with weight one (the ablation row "shared pool
               + layer aux"): unipool_pool_aux_loss is then called once per layer with L = 1, the losses
               are in loss_layers[L] and every layer's backward pass gets its own coefficients.
+    router    "norm": the NormRouter of Eq. 7; "softmax": the softmax router of the comparison rows (Sec. 5.4).
     lagged    App. F, one-step-behind: micro-batch m uses the usage statistic fbar of micro-batch
               m-1, held constant; the first micro-batch uses its own.  The statistic lives in two
               device buffers used in turn and is part of state_dict()."""
 
     def __init__(self, T, d_model, d_ff, E, k, L, dtype, c, eps, alpha_pool, device="cuda:0",
-                 wgrad="pool", recompute=False, lagged=False, aux="pool"):
-        assert wgrad in ("pool", "layer") and aux in ("pool", "layer")
+                 wgrad="pool", recompute=False, lagged=False, aux="pool", router="norm"):
+        assert wgrad in ("pool", "layer") and aux in ("pool", "layer") and router in ("norm", "softmax")
+        self.router = B.ROUTER_SOFTMAX if router == "softmax" else B.ROUTER_NORM
         assert not (lagged and aux == "layer"), "the lagged statistic belongs to the pool loss"
         self.aux = aux
         self.recompute, self.lagged = bool(recompute), bool(lagged)
@@ -122,7 +124,7 @@ class PoolStep:
     def shape(self, sigma: float, L=None) -> B.Shape:
         return B.Shape(T=self.T, d_model=self.d, d_ff=self.f, E=self.E, k=self.k, L=self.L if L is None else L,
                        dtype=self.dtype, sigma=float(sigma), c=self.c, eps=self.eps,
-                       alpha_pool=self.alpha)
+                       alpha_pool=self.alpha, router=self.router)
 
     def _call(self, fn, *args):
         if not self.timing:
