@@ -167,7 +167,7 @@ def run_workload(name, a, steps, warmup, keep=False):
     ps.timing = False
     res = dict(w=w, ms_step=dt / steps * 1e3, agg=agg, ps=ps)
     if keep:
-        res.update(xs=xs, wrs=wrs, gs=gs, wg=wg, wu=wu, wd=wd)
+        res.update(xs=xs, wrs=wrs, gs=gs, wg=wg, wu=wu, wd=wd, wgu=wgu)
     return res
 
 
@@ -225,6 +225,16 @@ def main():
     others["distinct_experts"] = {"GB/s": by_u / (ms_u * 1e-3) / 1e9, "frac": by_u / (ms_u * 1e-3) / 1e9 / PEAK_HBM_GBS,
                                   "avg_ms": ms_u, "algorithmic_bytes": by_u,
                                   "mean_distinct_per_token": float(dist_mean.item())}
+
+    # ---- forward pass alone, with the permuted copy and with the dispatch fused into the first GEMM
+    fwd = {}
+    for mode, gather in (("materialised", False), ("gathered", True)):
+        def fwd_all(gather=gather):
+            for l in range(w.L):
+                ps.forward_layer(l, r["xs"][l], r["wrs"][l], w.sigma, r["wgu"], r["wd"], gather=gather)
+        fwd[mode + "_ms_per_forward"] = timed(fwd_all, reps=3)
+    fwd["gather_speedup"] = fwd["materialised_ms_per_forward"] / fwd["gathered_ms_per_forward"]
+    others["forward_only_dispatch"] = fwd
 
     out = {
         "metric": "shared-pool MoE layer fwd+bwd tokens/s; grouped-GEMM % bf16 MFMA peak",

@@ -131,6 +131,8 @@ int unipool_route_bwd(const unipool_shape* shape, const void* x, const void* w_r
  *   x_perm[row_of_slot[t,j], :] = x[t, :].
  * in : x [T, d] act;  topk_idx [T, k];  counts [E] (from unipool_route)
  * out: x_perm [S, d] act;  expert_offsets [E+1];  row_of_slot [T, k];  slot_of_row [S].
+ * x_perm may be NULL (x is then not read): only the three index tensors are made, for a caller that
+ * runs the experts on gathered rows (unipool_expert_ffn_fwd_gather).
  */
 int unipool_permute(const unipool_shape* shape, const void* x, const int32_t* topk_idx,
                     const int32_t* counts, void* x_perm, int32_t* expert_offsets,
@@ -162,6 +164,19 @@ int unipool_expert_ffn_fwd(const unipool_shape* shape, const void* x_perm,
                            const int32_t* expert_offsets, const void* w_gate_up,
                            const void* w_down, void* act_a, void* act_b, void* act_h,
                            void* y_perm, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * unipool_expert_ffn_fwd with the dispatch fused into the first GEMM: the rows of expert e are read straight
+ * from the un-permuted x through slot_of_row (row r of the group order is token slot_of_row[r] / k), so no
+ * x_perm has to exist.  Meant for forward-only use; the weight gradient of the backward pass reads x_perm as
+ * a materialised operand.  Results are bit-identical to unipool_expert_ffn_fwd on the permuted copy.
+ * in : x [T, d] act;  slot_of_row [S], expert_offsets [E+1] (from unipool_permute);  weights as above.
+ * out: act_a, act_b, act_h [S, f] act;  y_perm [S, d] act.
+ */
+int unipool_expert_ffn_fwd_gather(const unipool_shape* shape, const void* x, const int32_t* slot_of_row,
+                                  const int32_t* expert_offsets, const void* w_gate_up, const void* w_down,
+                                  void* act_a, void* act_b, void* act_h, void* y_perm,
+                                  void* ws, size_t ws_bytes, void* stream);
 
 /*
  * First half of unipool_expert_ffn_fwd alone, for training with activation recomputation

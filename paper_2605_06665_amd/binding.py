@@ -29,7 +29,7 @@ class Shape(ctypes.Structure):
 
 
 ENTRY_POINTS = ("unipool_workspace_bytes", "unipool_last_error", "unipool_version", "unipool_route",
-                "unipool_route_bwd", "unipool_permute", "unipool_permute_static", "unipool_expert_ffn_fwd",
+                "unipool_route_bwd", "unipool_permute", "unipool_permute_static", "unipool_expert_ffn_fwd", "unipool_expert_ffn_fwd_gather",
                 "unipool_expert_ffn_recompute", "unipool_expert_ffn_bwd", "unipool_expert_wgrad", "unipool_combine",
                 "unipool_combine_bwd", "unipool_pool_aux_loss", "unipool_estimate_c",
                 "unipool_distinct_experts")
@@ -62,6 +62,7 @@ def load_library():
             "unipool_permute": [SP] + [P] * 7 + [P, Z, P],
             "unipool_permute_static": [SP] + [P] * 7 + [P],
             "unipool_expert_ffn_fwd": [SP] + [P] * 8 + [P, Z, P],
+            "unipool_expert_ffn_fwd_gather": [SP] + [P] * 9 + [P, Z, P],
             "unipool_expert_ffn_recompute": [SP] + [P] * 6 + [P, Z, P],
             "unipool_expert_ffn_bwd": [SP] + [P] * 12 + [P, Z, P],
             "unipool_expert_wgrad": [SP, I] + [P] * 7 + [I, P, Z, P],
@@ -162,6 +163,15 @@ def expert_ffn_fwd(shape, x_perm, expert_offsets, w_gate_up, w_down, act_a, act_
                                                  _ptr(w_gate_up), _ptr(w_down), _ptr(act_a),
                                                  _ptr(act_b), _ptr(act_h), _ptr(y_perm), p, n,
                                                  _stream(stream)), "unipool_expert_ffn_fwd")
+
+
+def expert_ffn_fwd_gather(shape, x, slot_of_row, expert_offsets, w_gate_up, w_down, act_a, act_b, act_h, y_perm, ws,
+                          stream=None):
+    p, n = _ws(ws)
+    _check(load_library().unipool_expert_ffn_fwd_gather(ctypes.byref(shape), _ptr(x), _ptr(slot_of_row),
+                                                        _ptr(expert_offsets), _ptr(w_gate_up), _ptr(w_down),
+                                                        _ptr(act_a), _ptr(act_b), _ptr(act_h), _ptr(y_perm), p, n,
+                                                        _stream(stream)), "unipool_expert_ffn_fwd_gather")
 
 
 def expert_ffn_recompute(shape, x_perm, expert_offsets, w_gate_up, act_a, act_b, act_h, ws, stream=None):

@@ -224,8 +224,9 @@ int unipool_permute(const unipool_shape* shape, const void* x, const int32_t* to
                     int32_t* row_of_slot, int32_t* slot_of_row, void* ws, size_t ws_bytes,
                     void* stream) {
     PROLOGUE();
-    REQUIRE_PTR(x); REQUIRE_PTR(topk_idx); REQUIRE_PTR(counts); REQUIRE_PTR(x_perm);
+    REQUIRE_PTR(topk_idx); REQUIRE_PTR(counts);
     REQUIRE_PTR(expert_offsets); REQUIRE_PTR(row_of_slot); REQUIRE_PTR(slot_of_row);
+    if (x_perm) REQUIRE_PTR(x);                       // x_perm == NULL: index maps only
     NEED_WS();
     const WsLayout w = ws_layout(*shape);
     hipError_t e = launch_permute(*shape, x, topk_idx, counts, x_perm, expert_offsets, row_of_slot,
@@ -252,6 +253,26 @@ int unipool_expert_ffn_fwd(const unipool_shape* shape, const void* x_perm,
         e = naive_ffn_fwd(*shape, x_perm, expert_offsets, w_gate_up, w_down, act_a, act_b, act_h,
                           y_perm, st);
     return check_hip(e, "unipool_expert_ffn_fwd");
+}
+
+int unipool_expert_ffn_fwd_gather(const unipool_shape* shape, const void* x, const int32_t* slot_of_row,
+                                  const int32_t* expert_offsets, const void* w_gate_up, const void* w_down,
+                                  void* act_a, void* act_b, void* act_h, void* y_perm, void* ws,
+                                  size_t ws_bytes, void* stream) {
+    PROLOGUE();
+    REQUIRE_PTR(x); REQUIRE_PTR(slot_of_row); REQUIRE_PTR(expert_offsets); REQUIRE_PTR(w_gate_up);
+    REQUIRE_PTR(w_down); REQUIRE_PTR(act_a); REQUIRE_PTR(act_b); REQUIRE_PTR(act_h); REQUIRE_PTR(y_perm);
+    NEED_WS();
+    const WsLayout w = ws_layout(*shape);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (mfma_ffn_supported(*shape) && !force_naive())
+        e = mfma_ffn_fwd(*shape, x, expert_offsets, w_gate_up, w_down, act_a, act_b, act_h, y_perm,
+                         (int32_t*)((char*)ws + w.tile_meta), st, slot_of_row);
+    else
+        e = naive_ffn_fwd(*shape, x, expert_offsets, w_gate_up, w_down, act_a, act_b, act_h, y_perm, st,
+                          slot_of_row);
+    return check_hip(e, "unipool_expert_ffn_fwd_gather");
 }
 
 int unipool_expert_ffn_recompute(const unipool_shape* shape, const void* x_perm,

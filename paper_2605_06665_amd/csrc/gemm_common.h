@@ -27,6 +27,9 @@ struct GemmArgs {
     int up_rows;          // EPI_SWIGLU_FWD: row offset of the up projection inside W_e (= d_ff)
     int group_m;          // row tiles walked together
     const void* zeros;    // >= 16 readable zero bytes (reduction tail of KTAIL kernels)
+    // gathered rows: row r of the grouped order is row gather[r] / gather_div of X (null: row r itself)
+    const int32_t* gather;
+    int gather_div;
     // ungrouped matrices (router): flat_rows > 0 replaces the tile table by row tiles of flat_bm rows
     int flat_rows, flat_bm;
     // EPI_ROUTE: outputs of the selection and its constants

@@ -219,7 +219,8 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
             const int q = (i * NW + wave) * 64 + lane;
             const int row = q / XT::CPR;
             const int cc = (q % XT::CPR) ^ XT::swz(row);
-            const int grow = t_row0 + min(row, t_rows - 1);
+            int grow = t_row0 + min(row, t_rows - 1);
+            if (g.gather != nullptr) grow = g.gather[grow] / g.gather_div;
             xsrc[i] = reinterpret_cast<const char*>(g.X + (size_t)grow * g.ldx + cc * 8);
             xload[i] = ((i * NW + wave) * 64 / XT::CPR) < ((t_rows + 7) & ~7);
         }
@@ -1234,7 +1235,7 @@ hipError_t mfma_route_fused(const unipool_shape& s, const void* x, const void* w
 
 hipError_t mfma_ffn_gate_up(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
                            const void* wgu, void* a_out, void* b_out, void* h_out, int32_t* tile_meta,
-                           hipStream_t st) {
+                           hipStream_t st, const int32_t* slot_of_row) {
     const int S = s.T * s.k, d = s.d_model, f = s.d_ff;
     const int max_tiles = S / kBM + s.E;
     hipError_t e = build_tiles(offsets, s.E, S, tile_meta, st);
@@ -1245,15 +1246,16 @@ hipError_t mfma_ffn_gate_up(const unipool_shape& s, const void* x_perm, const in
     a.K = d; a.N = f; a.n_tiles_n = cdiv(f, kBN / 2);
     a.tile_meta = tile_meta; a.out0 = a_out; a.out1 = b_out; a.out2 = h_out; a.ldo = f;
     a.up_rows = f;
+    a.gather = slot_of_row; a.gather_div = s.k;
     return run_xw<true, EPI_SWIGLU_FWD>(a, max_tiles, st);
 }
 
 hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
                         const void* wgu, const void* wd, void* a_out, void* b_out, void* h_out,
-                        void* y, int32_t* tile_meta, hipStream_t st) {
+                        void* y, int32_t* tile_meta, hipStream_t st, const int32_t* slot_of_row) {
     const int S = s.T * s.k, d = s.d_model, f = s.d_ff;
     const int max_tiles = S / kBM + s.E;
-    hipError_t e = mfma_ffn_gate_up(s, x_perm, offsets, wgu, a_out, b_out, h_out, tile_meta, st);
+    hipError_t e = mfma_ffn_gate_up(s, x_perm, offsets, wgu, a_out, b_out, h_out, tile_meta, st, slot_of_row);
     if (e != hipSuccess) return e;
     GemmArgs b = {};
     b.X = (const bf16*)h_out; b.ldx = f;

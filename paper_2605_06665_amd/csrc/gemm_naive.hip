@@ -30,16 +30,19 @@ __global__ void logits_kernel(const TA* __restrict__ x, const TA* __restrict__ w
 template <typename TA>
 __global__ void gate_up_kernel(const TA* __restrict__ xp, const int32_t* __restrict__ offsets,
                                const TA* __restrict__ wgu, int S, int d, int f, int E,
-                               TA* __restrict__ a, TA* __restrict__ b, TA* __restrict__ h) {
+                               TA* __restrict__ a, TA* __restrict__ b, TA* __restrict__ h,
+                               const int32_t* __restrict__ slot_of_row, int k) {
     const size_t id = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (id >= (size_t)S * f) return;
     const int row = (int)(id / f), n = (int)(id % f);
     const int e = expert_of_row(offsets, E, row);
     const TA* wg = wgu + ((size_t)e * 2 * f + n) * d;
     const TA* wu = wgu + ((size_t)e * 2 * f + f + n) * d;
+    // gathered dispatch: row r of the group order is token slot_of_row[r] / k of the un-permuted input
+    const size_t xrow = slot_of_row ? (size_t)(slot_of_row[row] / k) : (size_t)row;
     float av = 0.f, bv = 0.f;
     for (int c = 0; c < d; c++) {
-        const float xv = to_f32(xp[(size_t)row * d + c]);
+        const float xv = to_f32(xp[xrow * d + c]);
         av += xv * to_f32(wg[c]);
         bv += xv * to_f32(wu[c]);
     }
@@ -159,20 +162,21 @@ hipError_t naive_logits(const unipool_shape& s, const void* x, const void* w, fl
 
 hipError_t naive_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
                          const void* wgu, const void* wd, void* a, void* b, void* h, void* y,
-                         hipStream_t st) {
+                         hipStream_t st, const int32_t* slot_of_row) {
     const int S = s.T * s.k;
     DISPATCH((gate_up_kernel<TA><<<blocks_for((size_t)S * s.d_ff), 256, 0, st>>>(
-        (const TA*)x_perm, offsets, (const TA*)wgu, S, s.d_model, s.d_ff, s.E, (TA*)a, (TA*)b, (TA*)h)));
+        (const TA*)x_perm, offsets, (const TA*)wgu, S, s.d_model, s.d_ff, s.E, (TA*)a, (TA*)b, (TA*)h, slot_of_row, s.k)));
     DISPATCH((down_kernel<TA><<<blocks_for((size_t)S * s.d_model), 256, 0, st>>>(
         (const TA*)h, offsets, (const TA*)wd, S, s.d_model, s.d_ff, s.E, (TA*)y)));
     return hipGetLastError();
 }
 
 hipError_t naive_ffn_gate_up(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
-                            const void* wgu, void* a, void* b, void* h, hipStream_t st) {
+                            const void* wgu, void* a, void* b, void* h, hipStream_t st,
+                            const int32_t* slot_of_row) {
     const int S = s.T * s.k;
     DISPATCH((gate_up_kernel<TA><<<blocks_for((size_t)S * s.d_ff), 256, 0, st>>>(
-        (const TA*)x_perm, offsets, (const TA*)wgu, S, s.d_model, s.d_ff, s.E, (TA*)a, (TA*)b, (TA*)h)));
+        (const TA*)x_perm, offsets, (const TA*)wgu, S, s.d_model, s.d_ff, s.E, (TA*)a, (TA*)b, (TA*)h, slot_of_row, s.k)));
     return hipGetLastError();
 }
 

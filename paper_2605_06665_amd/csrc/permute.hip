@@ -162,6 +162,7 @@ __global__ __launch_bounds__(256) void permute_copy_kernel(const uint4* __restri
         row_of_slot[(size_t)t * k + lane] = r;
         slot_of_row[r] = t * k + lane;
     }
+    if (x_perm == nullptr) return;                 // index maps only
     const uint4* src = x + (size_t)t * row_chunks;
     for (int c0 = 0; c0 < row_chunks; c0 += 256) {
         uint4 v[4];
@@ -198,6 +199,7 @@ __global__ __launch_bounds__(64) void permute_copy_scalar_kernel(const uint32_t*
             row_of_slot[(size_t)t * k + j] = rows[j];
             slot_of_row[rows[j]] = t * k + j;
         }
+        if (x_perm == nullptr) continue;           // index maps only
         for (int c = lane; c < row_words; c += 64)
             x_perm[(size_t)rows[j] * row_words + c] = x[(size_t)t * row_words + c];
     }
@@ -235,7 +237,7 @@ extern "C" int unipool_permute_static(const unipool_shape* shape, const void* x,
     using namespace unipool;
     int rc = validate_shape(shape, __func__);
     if (rc) return rc;
-    if (!x || !topk_idx || !counts || !x_perm || !expert_offsets || !row_of_slot || !slot_of_row)
+    if (!topk_idx || !counts || !expert_offsets || !row_of_slot || !slot_of_row || (x_perm && !x))
         return set_error(UNIPOOL_EINVAL, "%s: a tensor argument is NULL", __func__);
     const size_t words = (size_t)cdiv(shape->T, 64) * (size_t)shape->E;
     if (words > kStaticHistWords)

@@ -137,13 +137,19 @@ class PoolStep:
         self.events.append((fn.__name__, e0, e1))
 
     # ------------------------------------------------------------------ forward
-    def forward_layer(self, l, x, w_router, sigma, w_gate_up, w_down):
+    def forward_layer(self, l, x, w_router, sigma, w_gate_up, w_down, gather=False):
+        """gather: forward-only dispatch without a permuted copy (index maps only; the first GEMM reads the rows
+        of x through slot_of_row).  The backward pass needs x_perm, so a training step leaves it off."""
         st, sh, ws = self.layers[l], self.shape(sigma), self.ws
         self._call(B.route, sh, x, w_router, st.topk_idx, st.topk_gate, st.logits, self.counts[l], self.psum[l], ws)
-        self._call(B.permute, sh, x, st.topk_idx, self.counts[l], st.x_perm, st.offsets, st.row_of_slot,
-                  st.slot_of_row, ws)
-        self._call(B.expert_ffn_fwd, sh, st.x_perm, st.offsets, w_gate_up, w_down, st.act_a, st.act_b, st.act_h,
-                         st.y_perm, ws)
+        self._call(B.permute, sh, None if gather else x, st.topk_idx, self.counts[l], None if gather else st.x_perm,
+                   st.offsets, st.row_of_slot, st.slot_of_row, ws)
+        if gather:
+            self._call(B.expert_ffn_fwd_gather, sh, x, st.slot_of_row, st.offsets, w_gate_up, w_down, st.act_a,
+                       st.act_b, st.act_h, st.y_perm, ws)
+        else:
+            self._call(B.expert_ffn_fwd, sh, st.x_perm, st.offsets, w_gate_up, w_down, st.act_a, st.act_b, st.act_h,
+                       st.y_perm, ws)
         self._call(B.combine, sh, st.y_perm, st.row_of_slot, st.topk_gate, st.out, ws)
         return st.out
 
