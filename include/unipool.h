@@ -5,7 +5,7 @@
  * The layer (paper Sec. 4.1, Eq. 2):  FFN_l(x) = sum_{i in Top-k(r_l(x))} g_{l,i}(x) e_i(x),
  * where the experts e_1..e_M form ONE pool shared by all L layers, every layer has
  * its own NormRouter r_l (Sec. 4.3, Eq. 7), and a pool-level auxiliary loss balances
- * expert usage summed over the layers (Sec. 4.2, Eq. 4-6; App. F).
+ * expert usage summed over the layers (Sec. 4.2, Eq. 4-6; App. G (pool auxiliary loss derivation)).
  *
  * General conventions
  *   - Every tensor pointer is a DEVICE pointer owned by the caller; tensors are
@@ -53,7 +53,7 @@ extern "C" {
 #define UNIPOOL_BF16 1
 
 /* Router kinds.  NORM is the paper's NormRouter (Sec. 4.3, Eq. 7).  SOFTMAX is the router of the comparison
- * rows (Sec. 3, Eq. 1 and Eq. 3; ablation "softmax router" of Sec. 5.4): score p_i = exp(z_i) / sum_j exp(z_j),
+ * rows (Sec. 4.1, Eq. 1 and Sec. 4.2, Eq. 3; ablation "softmax router" of Sec. 5.4): score p_i = exp(z_i) / sum_j exp(z_j),
  * selection of the k largest logits as for NORM, gate = p of the selected expert (no renormalisation over the
  * top-k), and the auxiliary losses take p as the routing probability.  sigma, c and eps are not used. */
 #define UNIPOOL_ROUTER_NORM    0
@@ -68,7 +68,7 @@ typedef struct unipool_shape {
     int32_t L;          /* layers sharing the pool (used by unipool_pool_aux_loss only) */
     int32_t dtype;      /* UNIPOOL_F32 or UNIPOOL_BF16 */
     float sigma;        /* NormRouter scale of THIS layer (learnable, init 1; Eq. 7) */
-    float c;            /* NormRouter calibration constant (App. G); a plain input */
+    float c;            /* NormRouter calibration constant (App. H (NormRouter Monte Carlo initialization)); a plain input */
     float eps;          /* NormRouter epsilon, added outside the norm (Eq. 7) */
     float alpha_pool;   /* pool auxiliary loss coefficient (Eq. 5) */
     int32_t router;     /* UNIPOOL_ROUTER_NORM or UNIPOOL_ROUTER_SOFTMAX (unipool_route, unipool_route_bwd) */
@@ -82,6 +82,18 @@ const char* unipool_last_error(void);
 
 /* Library version, major*10000 + minor*100 + patch. */
 int unipool_version(void);
+
+/*
+ * Which kernels a shape gets.  In bfloat16 mode the contractions run on the matrix cores (MFMA); shapes those
+ * kernels do not cover still give correct results, on plain one-thread-per-output kernels that are far slower:
+ * the router logits and the router backward when E is not a multiple of 8, and everything in float mode.
+ * Returns a bit mask: bit 0 the expert GEMMs use MFMA kernels, bit 1 the router contractions do, bit 2 the
+ * router runs as one fused kernel (logits, scores, top-k, statistics; E <= 256).  Negative on an invalid shape.
+ */
+#define UNIPOOL_FAST_EXPERTS      1
+#define UNIPOOL_FAST_ROUTER       2
+#define UNIPOOL_FAST_ROUTER_FUSED 4
+int unipool_fast_path(const unipool_shape* shape);
 
 /*
  * Router of one layer (Sec. 4.3, Eq. 7 and the top-k paragraph).
@@ -102,7 +114,7 @@ int unipool_route(const unipool_shape* shape, const void* x, const void* w_route
                   void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Backward of the router (derivative of Eq. 7 and of z = W h; App. F: the pool
+ * Backward of the router (derivative of Eq. 7 and of z = W h; App. G (pool auxiliary loss derivation): the pool
  * loss reaches parameters only through the scores).
  *   ds_{t,i} = aux_coef[i] (all i; omitted if aux_coef is NULL) + dgate[t,j] for i = topk_idx[t,j]
  *   d_sigma  = sum_{t,i} ds_{t,i} c max(0, zhat_{t,i});  dzhat = ds sigma c [zhat > 0]
@@ -180,7 +192,7 @@ int unipool_expert_ffn_fwd_gather(const unipool_shape* shape, const void* x, con
 
 /*
  * First half of unipool_expert_ffn_fwd alone, for training with activation recomputation
- * (App. C, hyperparameter details: activation checkpointing with MoE layer recompute): a caller that
+ * (App. D (hyperparameter details): activation checkpointing with MoE layer recompute): a caller that
  * did not keep A and B of a layer runs this before unipool_expert_ffn_bwd.  Same arithmetic as
  * in the forward pass, so the three tensors come out bit-identical to the forward's.
  * in : x_perm [S, d] act;  expert_offsets [E+1];  w_gate_up (see top).
@@ -252,10 +264,10 @@ int unipool_combine_bwd(const unipool_shape* shape, const void* dout, const void
 /*
  * Pool-level auxiliary loss over the L layers that share the pool (Sec. 4.2).
  *   pool_counts[i] = sum_l counts[l,i];   fbar_out[i] = pool_counts[i] / (L T k)   (Eq. 4)
- *   fbar = fbar_in if given (one-step-behind statistic of App. F) else fbar_out
+ *   fbar = fbar_in if given (one-step-behind statistic of App. G (pool auxiliary loss derivation)) else fbar_out
  *   loss = alpha_pool M sum_i fbar_i Pbar_i,  Pbar_i = (1/(L T)) sum_l psum[l,i]   (Eq. 5)
  *   aux_coef[i] = alpha_pool M fbar_i / (L T)  = d loss / d s^(l)_{t,i}             (Eq. 6)
- * fbar is a constant for differentiation (App. F).
+ * fbar is a constant for differentiation (App. G (pool auxiliary loss derivation)).
  * in : counts [L, E] int32;  psum [L, E] float;  fbar_in [E] float or NULL
  * out: pool_counts [E] int32;  fbar_out [E] float;  loss [1] float;  aux_coef [E] float.
  */
@@ -264,7 +276,7 @@ int unipool_pool_aux_loss(const unipool_shape* shape, const int32_t* counts, con
                           float* loss, float* aux_coef, void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Monte-Carlo estimate of the NormRouter calibration constant c (App. G, Alg. 1) from draws
+ * Monte-Carlo estimate of the NormRouter calibration constant c (App. H (NormRouter Monte Carlo initialization), Alg. 1) from draws
  * the caller supplies: for every row x of samples, y = relu(x / ||x||_2), the k largest
  * components of y, 1 / their 2-norm; c is the mean over the rows.  A row without a positive
  * component has an all-zero top-k part and is left out (the paper does not treat 1/0);
@@ -279,7 +291,7 @@ int unipool_estimate_c(int E, int k, const float* samples, int n_samples, float*
                        int32_t* samples_used, void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Distinct pool experts per token (App. D): U(t) = number of different experts token t
+ * Distinct pool experts per token (App. E (distinct-expert accounting)): U(t) = number of different experts token t
  * selects over n_layers layers that route into one pool (all k selections of a layer count;
  * the paper states it for top-1), and its mean over the tokens.
  * in : topk_idx_l: device array of n_layers device pointers, each to a [T, k] int32 tensor

@@ -28,9 +28,9 @@ dense SwiGLU MLP; the softmax router (comparison rows of Sec. 5.4) by rows summi
 pool loss equal to alpha under exactly uniform usage, shift invariance and finite differences;
 the one-step-behind loop against a hand count of the previous
 micro-batch's slots and finite differences of the lagged objective; the
-recompute half against the forward record.  `c_from_samples` (App. G, Alg. 1) is pinned by
+recompute half against the forward record.  `c_from_samples` (App. H (NormRouter Monte Carlo initialization), Alg. 1) is pinned by
 loops on small draws and closed cases, `estimate_c` statistically; `distinct_experts`
-(App. D) by hand cases and the occupancy closed form for uniform routing.
+(App. E (distinct-expert accounting)) by hand cases and the occupancy closed form for uniform routing.
 """
 from __future__ import annotations
 
@@ -56,7 +56,7 @@ def norm_router_scores(z, sigma, c, eps):
 
 
 def softmax_router_scores(z):
-    """The softmax router of the comparison rows (Sec. 3, Eq. 1 and Eq. 3; Sec. 5.4 ablation
+    """The softmax router of the comparison rows (Sec. 4.1, Eq. 1 and Sec. 4.2, Eq. 3; Sec. 5.4 ablation
     "softmax router"): p_i = exp(z_i) / sum_j exp(z_j).  The gate of a selected expert is
     its probability p_i (no renormalisation over the top-k: with the paper's top-1 routing a
     renormalised gate would be the constant 1 and the router would get no gradient from
@@ -214,13 +214,13 @@ def moe_layer_fwd(x, w_router, w_gate, w_up, w_down, k, sigma, c, eps, idx=None,
 
 
 # ---------------------------------------------------------------------------
-# Pool-level auxiliary loss (Sec. 4.2, Eq. 4-6; App. F)
+# Pool-level auxiliary loss (Sec. 4.2, Eq. 4-6; App. G (pool auxiliary loss derivation))
 # ---------------------------------------------------------------------------
 def pool_aux_loss(counts, psum, T, k, alpha, fbar_in=None):
     """counts [L,E] slot counts, psum [L,E] score sums.
 
     f_i^(l) = counts/(T k);  fbar = mean_l f^(l)   (Eq. 4), unless a lagged
-    fbar is supplied (App. F, one-step-behind: fbar is a constant either way);
+    fbar is supplied (App. G (pool auxiliary loss derivation), one-step-behind: fbar is a constant either way);
     P_i^(l) = psum/T;  Pbar = mean_l P^(l);
     loss = alpha * M * sum_i fbar_i * Pbar_i        (Eq. 5).
     coef_i = d loss / d s_{t,i}^(l) = alpha * M * fbar_i / (L T)   (from Eq. 6).
@@ -248,7 +248,7 @@ def pool_aux_loss_decomposed(counts, psum, T, k, alpha, fbar_in=None):
 
 
 # ---------------------------------------------------------------------------
-# Backward (derivatives of Eq. 2, Eq. 7 and Eq. 6; App. F: only the routing
+# Backward (derivatives of Eq. 2, Eq. 7 and Eq. 6; App. G (pool auxiliary loss derivation): only the routing
 # scores carry the auxiliary gradient)
 # ---------------------------------------------------------------------------
 def combine_bwd(dout, y_perm, row_of_slot, gate):
@@ -410,7 +410,7 @@ def pool_groups_step(groups, k, c, eps, alpha):
 
 
 def micro_batch_loop(batches, w_routers, w_gate, w_up, w_down, k, sigmas, c, eps, alpha, fbar0=None):
-    """App. F, one-step-behind: micro-batch m takes the usage statistic fbar of micro-batch
+    """App. G (pool auxiliary loss derivation), one-step-behind: micro-batch m takes the usage statistic fbar of micro-batch
     m-1 as a constant; the first one takes `fbar0`, or, when that is None, its own (the
     paper does not say what the first micro-batch uses).  `batches` is a list of
     (xs, grad_outs).  Returns the list of pool_step results; entry m's "fbar" is the
@@ -426,7 +426,7 @@ def micro_batch_loop(batches, w_routers, w_gate, w_up, w_down, k, sigmas, c, eps
 
 
 def objective(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps, alpha, fbar, router="norm"):
-    """Lambda = sum_l <Out^(l), G^(l)> + L_pool with fbar held constant (App. F)."""
+    """Lambda = sum_l <Out^(l), G^(l)> + L_pool with fbar held constant (App. G (pool auxiliary loss derivation))."""
     total = 0.0
     psum = []
     for l in range(len(xs)):
@@ -441,10 +441,10 @@ def objective(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps,
 
 
 # ---------------------------------------------------------------------------
-# App. G, Alg. 1: Monte-Carlo estimate of the NormRouter constant c
+# App. H (NormRouter Monte Carlo initialization), Alg. 1: Monte-Carlo estimate of the NormRouter constant c
 # ---------------------------------------------------------------------------
 def c_from_samples(samples, k):
-    """App. G, Alg. 1 on given draws x ~ N(0, I_E), one per row: for every row
+    """App. H (NormRouter Monte Carlo initialization), Alg. 1 on given draws x ~ N(0, I_E), one per row: for every row
     y = relu(x / ||x||_2), the k largest components of y, 1 / their 2-norm; c is the mean.
     Rows whose top-k part is all zero (1/0) are dropped; the paper does not treat that
     case.  Returns (c, rows_used)."""
@@ -463,10 +463,10 @@ def estimate_c(E, k, n_samples=100_000, seed=0):
 
 
 # ---------------------------------------------------------------------------
-# App. D: distinct experts touched by a token over the layers that share a pool
+# App. E (distinct-expert accounting): distinct experts touched by a token over the layers that share a pool
 # ---------------------------------------------------------------------------
 def distinct_experts(idx_layers):
-    """U(x) = | { experts selected for token x at any of the L layers } |  (App. D; stated
+    """U(x) = | { experts selected for token x at any of the L layers } |  (App. E (distinct-expert accounting); stated
     there for top-1, taken here over all k selections of every layer).
     idx_layers: L arrays [T, k].  Returns (U [T] int64, mean of U)."""
     idx = np.stack([np.asarray(i) for i in idx_layers], axis=1)      # [T, L, k]

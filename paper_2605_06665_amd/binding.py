@@ -28,7 +28,7 @@ class Shape(ctypes.Structure):
                 ("eps", ctypes.c_float), ("alpha_pool", ctypes.c_float), ("router", ctypes.c_int32)]
 
 
-ENTRY_POINTS = ("unipool_workspace_bytes", "unipool_last_error", "unipool_version", "unipool_route",
+ENTRY_POINTS = ("unipool_workspace_bytes", "unipool_last_error", "unipool_version", "unipool_fast_path", "unipool_route",
                 "unipool_route_bwd", "unipool_permute", "unipool_permute_static", "unipool_expert_ffn_fwd", "unipool_expert_ffn_fwd_gather",
                 "unipool_expert_ffn_recompute", "unipool_expert_ffn_bwd", "unipool_expert_wgrad", "unipool_combine",
                 "unipool_combine_bwd", "unipool_pool_aux_loss", "unipool_estimate_c",
@@ -56,6 +56,8 @@ def load_library():
         lib.unipool_last_error.argtypes = []
         lib.unipool_version.restype = I
         lib.unipool_version.argtypes = []
+        lib.unipool_fast_path.restype = I
+        lib.unipool_fast_path.argtypes = [SP]
         sigs = {
             "unipool_route": [SP] + [P] * 7 + [P, Z, P],
             "unipool_route_bwd": [SP] + [P] * 9 + [I, P, Z, P],
@@ -86,6 +88,14 @@ def last_error() -> str:
 
 def version() -> int:
     return load_library().unipool_version()
+
+
+def fast_path(shape: Shape) -> int:
+    """Bit mask of the kernel families the shape gets (bit 0 expert GEMMs on MFMA, bit 1 router contractions on
+    MFMA, bit 2 fused router kernel)."""
+    rc = load_library().unipool_fast_path(ctypes.byref(shape))
+    _check(rc if rc < 0 else 0, "unipool_fast_path")
+    return rc
 
 
 def _ptr(t) -> Optional[int]:

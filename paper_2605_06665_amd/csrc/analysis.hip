@@ -1,6 +1,6 @@
 // Analysis observables of the paper, on the device:
-//   * Monte-Carlo estimate of the NormRouter constant c from given normal draws (App. G, Alg. 1);
-//   * U(x), the number of distinct pool experts a token selects over the L layers (App. D).
+//   * Monte-Carlo estimate of the NormRouter constant c from given normal draws (App. H (NormRouter Monte Carlo initialization), Alg. 1);
+//   * U(x), the number of distinct pool experts a token selects over the L layers (App. E (distinct-expert accounting)).
 #include "kernels.h"
 
 namespace unipool {

@@ -161,7 +161,13 @@ size_t unipool_workspace_bytes(const unipool_shape* shape) {
 
 const char* unipool_last_error(void) { return g_err; }
 
-int unipool_version(void) { return 100; }
+int unipool_version(void) { return 200; }
+
+int unipool_fast_path(const unipool_shape* shape) {
+    PROLOGUE();
+    return (mfma_ffn_supported(*shape) ? UNIPOOL_FAST_EXPERTS : 0) | (mfma_router_supported(*shape) ? UNIPOOL_FAST_ROUTER : 0) |
+           (mfma_route_fused_supported(*shape) ? UNIPOOL_FAST_ROUTER_FUSED : 0);
+}
 
 int unipool_route(const unipool_shape* shape, const void* x, const void* w_router,
                   int32_t* topk_idx, float* topk_gate, float* logits, int32_t* counts, float* psum,

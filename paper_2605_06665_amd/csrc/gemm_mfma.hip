@@ -1339,7 +1339,9 @@ hipError_t mfma_route_bwd_mm(const unipool_shape& s, const void* x, const void* 
     reduce_partials_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(wpart, used, n, dw);
     // dx (+)= dz W   (W is [E][d]: reduction index strided)
     GemmArgs b = {};
-    b.flat_rows = T; b.flat_bm = kFlatBM;
+    // 256-row tiles where they still give every CU a tile: the short reduction (E indices) makes the pipeline
+    // fill of a tile as long as its loop, and a taller tile pays it once for twice the rows
+    b.flat_rows = T; b.flat_bm = (cdiv(T, kBM) * cdiv(d, kBN) >= num_cus()) ? kBM : kFlatBM;
     b.X = (const bf16*)dz; b.ldx = E;
     b.W = (const bf16*)w; b.w_stride = 0; b.ldw = d;
     b.K = E; b.N = d; b.n_tiles_n = cdiv(d, kBN);

@@ -45,14 +45,14 @@ class PoolStep:
     wgrad     "pool": one weight-gradient pass over all layers at the end of the backward pass;
               "layer": accumulate into the float gradients layer by layer.
     recompute keep one shared pair of A / B buffers instead of one per layer and rebuild a layer's
-              A and B (unipool_expert_ffn_recompute) right before its backward pass (App. C:
+              A and B (unipool_expert_ffn_recompute) right before its backward pass (App. D (hyperparameter details):
               activation checkpointing with MoE recompute).  Results are bit-identical.
     aux       "pool": the pool-level loss (Eq. 5) over all L layers; "layer": the per-layer loss
               (Eq. 3) for every layer on its own, each with weight one (the ablation row "shared pool
               + layer aux"): unipool_pool_aux_loss is then called once per layer with L = 1, the losses
               are in loss_layers[L] and every layer's backward pass gets its own coefficients.
     router    "norm": the NormRouter of Eq. 7; "softmax": the softmax router of the comparison rows (Sec. 5.4).
-    lagged    App. F, one-step-behind: micro-batch m uses the usage statistic fbar of micro-batch
+    lagged    App. G (pool auxiliary loss derivation), one-step-behind: micro-batch m uses the usage statistic fbar of micro-batch
               m-1, held constant; the first micro-batch uses its own.  The statistic lives in two
               device buffers used in turn and is part of state_dict()."""
 

@@ -53,7 +53,7 @@ class Workload:
     dtype: str      # "f32" or "bf16"
     seed: int
     sigma: float = 1.0       # NormRouter learnable scale at init (Sec. 4.3)
-    c: float = 1.0           # NormRouter calibration constant (App. G), an input here
+    c: float = 1.0           # NormRouter calibration constant (App. H (NormRouter Monte Carlo initialization)), an input here
     eps: float = 1e-6        # NormRouter epsilon
     alpha: float = 1e-2      # pool auxiliary loss coefficient (Table 8)
     skew: str = "none"       # "none" | "hot" | "hot_shared" | "zipf"
@@ -66,7 +66,7 @@ class Workload:
         return replace(self, **kw)
 
 
-# c(E, k): Monte-Carlo estimates of App. G's expectation (2e5 samples); they are
+# c(E, k): Monte-Carlo estimates of App. H (NormRouter Monte Carlo initialization)'s expectation (2e5 samples); they are
 # plain inputs to both the oracle and the GPU path.
 WORKLOADS: Dict[str, Workload] = {
     "C1": Workload("C1-tiny-f32", L=2, E=8, d=64, f=128, k=2, T=128, dtype="f32",

@@ -1,5 +1,5 @@
-"""GPU parity of the analysis observables: Alg. 1 on given draws (App. G) and the distinct-expert
-count U(x) (App. D), through the C ABI, against the oracle."""
+"""GPU parity of the analysis observables: Alg. 1 on given draws (App. H (NormRouter Monte Carlo initialization)) and the distinct-expert
+count U(x) (App. E (distinct-expert accounting)), through the C ABI, against the oracle."""
 import numpy as np
 import pytest
 

@@ -1,5 +1,5 @@
-"""GPU parity of the stateful micro-batch loop: the one-step-behind usage statistic (App. F) against
-the oracle's loop, its checkpoint, and the recompute mode (App. C), whose results must be bitwise
+"""GPU parity of the stateful micro-batch loop: the one-step-behind usage statistic (App. G (pool auxiliary loss derivation)) against
+the oracle's loop, its checkpoint, and the recompute mode (App. D (hyperparameter details)), whose results must be bitwise
 those of the mode that keeps the activations; and of the sharing-scope variants of Sec. 5.4 (per-layer
 loss on the shared pool, pool groups over depth)."""
 import numpy as np

@@ -62,3 +62,17 @@ def test_null_arguments_fail_before_any_launch(U):
     with pytest.raises(U.UniPoolError, match="NULL"):
         U.pool_aux_loss(sh, None, None, None, None, None, None, None, stream=0)
     assert "NULL" in U.last_error()
+
+
+def test_fast_path_reports_the_kernel_families(U):
+    def sh(**kw):
+        base = dict(T=512, d_model=128, d_ff=192, E=64, k=2, L=2, dtype=U.BF16, sigma=1.0, c=2.5, eps=1e-6,
+                    alpha_pool=0.01)
+        base.update(kw)
+        return U.Shape(**base)
+    assert U.fast_path(sh()) == 7                       # MFMA experts, MFMA router, fused router
+    assert U.fast_path(sh(E=512)) == 3                  # a pool beyond the fused router's 256 experts
+    assert U.fast_path(sh(E=10)) == 1                   # E not a multiple of 8: plain router kernels
+    assert U.fast_path(sh(dtype=U.F32)) == 0            # float mode: plain kernels throughout
+    with pytest.raises(U.UniPoolError, match="k=9"):
+        U.fast_path(sh(k=9))

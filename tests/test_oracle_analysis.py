@@ -1,5 +1,5 @@
-"""Pins for the oracle's analysis observables: Alg. 1 on given draws (App. G) and the
-distinct-expert count U(x) (App. D)."""
+"""Pins for the oracle's analysis observables: Alg. 1 on given draws (App. H (NormRouter Monte Carlo initialization)) and the
+distinct-expert count U(x) (App. E (distinct-expert accounting))."""
 import math
 
 import numpy as np

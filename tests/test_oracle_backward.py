@@ -1,6 +1,6 @@
 """Pins for the oracle's backward pass: central finite differences of its own
 float64 forward objective, an independent derivation by torch's autograd on a
-torch-typed restatement of Eq. 2 / Eq. 7, and structural facts from App. F."""
+torch-typed restatement of Eq. 2 / Eq. 7, and structural facts from App. G (pool auxiliary loss derivation)."""
 import numpy as np
 import pytest
 
@@ -50,7 +50,7 @@ def test_all_gradients_by_central_differences():
             break
         seed += 1
     step = O.pool_step(xs, wrs, wg, wu, wd, gs, HP["k"], sigmas, HP["c"], HP["eps"], HP["alpha"])
-    fbar = step["fbar"].copy()                      # constant for differentiation (App. F)
+    fbar = step["fbar"].copy()                      # constant for differentiation (App. G (pool auxiliary loss derivation))
 
     def lam():
         return O.objective(xs, wrs, wg, wu, wd, gs, HP["k"], sigmas, HP["c"], HP["eps"],
@@ -122,7 +122,7 @@ def test_backward_against_autograd():
 
 
 def test_aux_loss_reaches_only_the_router():
-    # App. F: only the routing scores carry the pool-loss gradient.
+    # App. G (pool auxiliary loss derivation): only the routing scores carry the pool-loss gradient.
     xs, wrs, wg, wu, wd, gs, sigmas = problem(seed=4)
     zero_g = [np.zeros_like(g) for g in gs]
     step = O.pool_step(xs, wrs, wg, wu, wd, zero_g, HP["k"], sigmas, HP["c"], HP["eps"], HP["alpha"])

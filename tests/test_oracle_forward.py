@@ -249,7 +249,7 @@ def test_counts_sum_and_pool_totals():
     assert float(fbar.sum()) == pytest.approx(1.0, abs=1e-14)
 
 
-# ------------------------------------------------------------------ App. G
+# ------------------------------------------------------------------ App. H (NormRouter Monte Carlo initialization)
 def test_estimate_c_calibrates_selected_scores():
     # definition of c: mean over tokens of 1/||gate/(sigma c)||_2 on Gaussian logits ~ c
     E, k = 64, 2

@@ -1,5 +1,5 @@
-"""Pins for the oracle's one-step-behind micro-batch loop (App. F) and for the recompute half of
-the expert FFN (App. C).  None of them calls the function under test to make its own expectation:
+"""Pins for the oracle's one-step-behind micro-batch loop (App. G (pool auxiliary loss derivation)) and for the recompute half of
+the expert FFN (App. D (hyperparameter details)).  None of them calls the function under test to make its own expectation:
 the lagged statistic is counted by hand with Python loops, the gradients come from central finite
 differences of the float64 objective, the recompute is compared with a dense per-row evaluation.
 The sharing-scope variants of Sec. 5.4 (per-layer loss on a shared pool, pool groups) are pinned by
