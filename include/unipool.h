@@ -88,7 +88,8 @@ int unipool_version(void);
  * kernels do not cover still give correct results, on plain one-thread-per-output kernels that are far slower:
  * the router logits and the router backward when E is not a multiple of 8, and everything in float mode.
  * Returns a bit mask: bit 0 the expert GEMMs use MFMA kernels, bit 1 the router contractions do, bit 2 the
- * router runs as one fused kernel (logits, scores, top-k, statistics; E <= 256).  Negative on an invalid shape.
+ * router runs as one fused kernel (logits, scores, top-k, statistics: d_model a multiple of 128, E a multiple
+ * of 8 and at most 512).  Negative on an invalid shape.
  */
 #define UNIPOOL_FAST_EXPERTS      1
 #define UNIPOOL_FAST_ROUTER       2

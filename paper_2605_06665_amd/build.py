@@ -12,7 +12,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libunipool.so")
-SOURCES = ["api.hip", "router.hip", "permute.hip", "combine.hip", "aux_loss.hip", "analysis.hip", "gemm_naive.hip",
+SOURCES = ["api.hip", "router.hip", "router_fused.hip", "permute.hip", "combine.hip", "aux_loss.hip", "analysis.hip", "gemm_naive.hip",
            "gemm_mfma.hip"]
 
 def _hipcc() -> str:

@@ -166,7 +166,7 @@ int unipool_version(void) { return 200; }
 int unipool_fast_path(const unipool_shape* shape) {
     PROLOGUE();
     return (mfma_ffn_supported(*shape) ? UNIPOOL_FAST_EXPERTS : 0) | (mfma_router_supported(*shape) ? UNIPOOL_FAST_ROUTER : 0) |
-           (mfma_route_fused_supported(*shape) ? UNIPOOL_FAST_ROUTER_FUSED : 0);
+           (router_fused_supported(*shape) ? UNIPOOL_FAST_ROUTER_FUSED : 0);
 }
 
 int unipool_route(const unipool_shape* shape, const void* x, const void* w_router,
@@ -181,11 +181,11 @@ int unipool_route(const unipool_shape* shape, const void* x, const void* w_route
     hipStream_t st = (hipStream_t)stream;
     float* z = logits ? logits : (float*)(base + w.dz);
     hipError_t e;
-    if (mfma_route_fused_supported(*shape) && !force_naive() && !unfused_router()) {
+    if (router_fused_supported(*shape) && !force_naive() && !unfused_router()) {
         // logits, scores, top-k and block statistics in one kernel; then the sum over the blocks
         int32_t* cnt_part = (int32_t*)(base + w.dsigma_part);
         float* psum_part = (float*)(base + w.psum_part);
-        e = mfma_route_fused(*shape, x, w_router, z, topk_idx, topk_gate, cnt_part, psum_part, st);
+        e = router_fused(*shape, x, w_router, z, topk_idx, topk_gate, cnt_part, psum_part, st);
         if (e != hipSuccess) return check_hip(e, "unipool_route: fused router");
         return check_hip(launch_route_finalize(*shape, cnt_part, psum_part, counts, psum, st),
                          "unipool_route: statistics");

@@ -32,14 +32,6 @@ struct GemmArgs {
     int gather_div;
     // ungrouped matrices (router): flat_rows > 0 replaces the tile table by row tiles of flat_bm rows
     int flat_rows, flat_bm;
-    // EPI_ROUTE: outputs of the selection and its constants
-    int32_t* topk_idx;
-    float* topk_gate;
-    int32_t* cnt_part;
-    float* psum_part;
-    int topk;
-    float sigma_c, eps;
-    int softmax;          // EPI_ROUTE: softmax router instead of the NormRouter
     // Meeting point of the two workgroups that run the two row tiles of an expert side by side (one
     // zeroed counter per pair of list positions, or null): they start their tiles together, so the
     // weight tile one of them fetches is still in L2 when the other asks for it.
@@ -60,7 +52,6 @@ constexpr int EPI_STORE = 0;       // bf16 store (optionally added to the destin
 constexpr int EPI_SWIGLU_FWD = 1;  // tile = [gate | up] columns; writes A, B, H = silu(A)*B
 constexpr int EPI_SWIGLU_BWD = 2;  // acc = dH; reads A, B; writes dA | dB
 constexpr int EPI_F32 = 3;         // float store
-constexpr int EPI_ROUTE = 4;       // acc = logits: float store, then NormRouter scores, top-k and statistics
 
 constexpr int kNumXcd = 8;
 
@@ -187,7 +178,7 @@ template <int EPI> struct Staging {
     static constexpr int SROW = SC * 2 + 16;                    // row stride in bytes
     static constexpr int WSTG = (EPI == EPI_SWIGLU_BWD ? 2 : 1) * 32 * SROW;   // bytes per wavefront
     static constexpr int RW = 32768 / WSTG < kXwWaves ? 32768 / WSTG : kXwWaves;
-    static constexpr int REGIONS = (EPI == EPI_F32 || EPI == EPI_ROUTE) ? 0 : (kXwWaves + RW - 1) / RW;
+    static constexpr int REGIONS = (EPI == EPI_F32) ? 0 : (kXwWaves + RW - 1) / RW;
     static constexpr bool PREW1 = REGIONS <= 2;
     static_assert(REGIONS <= 3, "three operand buffers are free in the epilogue");
 };

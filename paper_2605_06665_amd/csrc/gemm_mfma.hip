@@ -26,7 +26,6 @@
 //     side by side so that they share its weight tiles in L2, and lets a workgroup request the first
 //     stages of its next tile before the epilogue of the current one.
 #include "gemm_common.h"
-#include "route_select.h"
 
 namespace unipool {
 
@@ -56,14 +55,6 @@ __device__ unsigned long long g_phase_times[1024][8];
 #endif
 
 
-// EPI_ROUTE keeps the float logits of a tile of up to 128 tokens in LDS: rows of kRouteLdz floats,
-// then the score sums of the eight wavefronts and the selection counts of the two 64-token blocks.
-constexpr int kRouteRows = 128;
-constexpr int kRouteMaxE = 256;
-constexpr int kRouteLdz = kRouteMaxE + 4;
-constexpr int kRoutePsOff = kRouteRows * kRouteLdz * 4;
-constexpr int kRouteCntOff = kRoutePsOff + 8 * kRouteMaxE * 4;
-static_assert(kRouteCntOff + 2 * kRouteMaxE * 4 <= 160 * 1024, "router tile and statistics fit LDS");
 
 
 
@@ -476,7 +467,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     // The buffers of the last stage become the staging space of the epilogue; the others take the
     // first stages of the next tile now, so that its pipeline is full when the epilogue ends.
     constexpr bool PREW1 = Staging<EPI>::PREW1;
-    if constexpr (!KTAIL && EPI != EPI_ROUTE) {
+    if constexpr (!KTAIL) {
         if (nxt.valid) {
             set_sources(nxt.expert, nxt.row0, nxt.rows, nxt.nt);
 #pragma unroll
@@ -497,25 +488,7 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     // ---- epilogue ---------------------------------------------------------------------------------
     // acc[tm][mh][nb][r] = C[row (wm + 2 tm)*32 + 16 mh + lane%16][column 16 nb + 4*(lane/16) + r of the wavefront's 64]
 
-    if constexpr (EPI == EPI_ROUTE) {
-        // the logits of the tile go to LDS in float; the selection follows once all wavefronts are done
-        float* tile = reinterpret_cast<float*>(smem);
-#pragma unroll
-        for (int tm = 0; tm < MTV; tm++)
-#pragma unroll
-            for (int mh = 0; mh < 2; mh++) {
-                if (LH && tm == MTV - 1 && mh == 1) continue;
-                const int r_in = (wm + 2 * tm) * 32 + 16 * mh + l16;
-                if (r_in < kRouteRows) {
-#pragma unroll
-                    for (int nb = 0; nb < 4; nb++) {
-                        const int col = wpos[nb >> 1] + 16 * (nb & 1) + 4 * lg;
-                        *reinterpret_cast<float4*>(tile + r_in * kRouteLdz + col) =
-                            make_float4(acc[tm][mh][nb][0], acc[tm][mh][nb][1], acc[tm][mh][nb][2], acc[tm][mh][nb][3]);
-                    }
-                }
-            }
-    } else if constexpr (EPI == EPI_F32) {
+    if constexpr (EPI == EPI_F32) {
         float* out = reinterpret_cast<float*>(g.out0);
 #pragma unroll
         for (int tm = 0; tm < MTV; tm++)
@@ -547,64 +520,6 @@ __device__ __forceinline__ void xw_tile(const GemmArgs& g, char* smem, TileRef c
     }
     PHASE_STAMP(t_end);
     PHASE_COMMIT(t_begin, t_filled, t_looped, t_end);
-}
-
-// Second half of EPI_ROUTE, run by all wavefronts once the tile's logits are in LDS: logits to
-// global memory as whole rows, then per token norm, scores, top-k and gates (the stand-alone top-k
-// kernel's code and token-to-wavefront assignment: wavefront w owns tokens 16w .. 16w+15 of the
-// tile, four wavefronts make one 64-token block of the statistics).
-template <int GS, int VPL>
-__device__ __forceinline__ void route_epilogue(const GemmArgs& g, char* smem, const TileRef& cur) {
-    constexpr int TPW = 64 / GS;
-    const float* tile = reinterpret_cast<const float*>(smem);
-    float* lds_ps = reinterpret_cast<float*>(smem + kRoutePsOff);
-    int* lds_cnt = reinterpret_cast<int*>(smem + kRouteCntOff);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int grp = lane / GS, sl = lane % GS;
-    const int E = g.N, rows = cur.rows, row0 = cur.row0;
-    for (int i = tid; i < 2 * kRouteMaxE; i += kXwThreads) lds_cnt[i] = 0;
-    float* zout = reinterpret_cast<float*>(g.out0);
-    const int c4n = E / 4;                                 // E is a multiple of 8 here
-    for (int id = tid; id < rows * c4n; id += kXwThreads) {
-        const int r = id / c4n, c4 = id % c4n;
-        *reinterpret_cast<float4*>(zout + (size_t)(row0 + r) * g.ldo + 4 * c4) =
-            *reinterpret_cast<const float4*>(tile + r * kRouteLdz + 4 * c4);
-    }
-    lds_barrier();
-    float ps[VPL];
-#pragma unroll
-    for (int i = 0; i < VPL; i++) ps[i] = 0.f;
-    for (int tt = 0; tt < 16; tt += TPW) {
-        const int lr = wave * 16 + tt + grp;
-        const float* zr = tile + min(lr, rows - 1) * kRouteLdz;
-        float z[VPL];
-#pragma unroll
-        for (int i = 0; i < VPL; i++) {
-            const int e = sl + GS * i;
-            z[i] = (e < E) ? zr[e] : 0.f;
-        }
-        route_select<GS, VPL>(z, sl, E, g.topk, g.sigma_c, g.eps, g.softmax != 0, lr < rows, (size_t)(row0 + lr), g.topk_idx,
-                              g.topk_gate, lds_cnt + (wave >> 2) * kRouteMaxE, ps);
-    }
-#pragma unroll
-    for (int i = 0; i < VPL; i++) {
-#pragma unroll
-        for (int o = GS; o < 64; o <<= 1) ps[i] += __shfl_xor(ps[i], o, 64);
-        if (grp == 0 && sl + GS * i < kRouteMaxE) lds_ps[wave * kRouteMaxE + sl + GS * i] = ps[i];
-    }
-    lds_barrier();
-    const int nblocks = (g.flat_rows + 63) / 64;
-    const int e = tid & (kRouteMaxE - 1), half = tid >> 8;          // 512 threads: two blocks of 64 tokens
-    const int blk = row0 / 64 + half;
-    if (e < E && blk < nblocks && half * 64 < rows) {
-        const float* p = lds_ps + (4 * half) * kRouteMaxE + e;
-        float v = p[0];
-        v += p[kRouteMaxE];
-        v += p[2 * kRouteMaxE];
-        v += p[3 * kRouteMaxE];
-        g.psum_part[(size_t)blk * E + e] = v;
-        g.cnt_part[(size_t)blk * E + e] = lds_cnt[half * kRouteMaxE + e];
-    }
 }
 
 template <int BM, int BN, int BK, int NS, bool WK, int EPI, bool KTAIL>
@@ -712,13 +627,8 @@ __global__ __launch_bounds__(kXwThreads) void gemm_xw_kernel(const GemmArgs g) {
             case 9: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4, true>(g, smem, cur, nxt, pre, g0); break;
             default: xw_tile<BM, BN, BK, NS, WK, EPI, KTAIL, 4, false>(g, smem, cur, nxt, pre, g0); break;
         }
-        if constexpr (EPI == EPI_ROUTE) {
-            lds_barrier();            // the tile's logits are complete in LDS
-            if (g.N <= 128) route_epilogue<16, 8>(g, smem, cur);
-            else route_epilogue<16, 16>(g, smem, cur);
-        }
         lds_barrier();                // the staging space is free: the next tile may load into it
-        pre = (!KTAIL && EPI != EPI_ROUTE && nxt.valid) ? ((Staging<EPI>::PREW1 && nk > 1) ? 3 : 1) : 0;
+        pre = (!KTAIL && nxt.valid) ? ((Staging<EPI>::PREW1 && nk > 1) ? 3 : 1) : 0;
         g0 = (g0 + nk) % 6;           // the buffers repeat with period 2 and 3
         cur = nxt;
     }
@@ -1212,25 +1122,6 @@ hipError_t mfma_logits(const unipool_shape& s, const void* x, const void* w, flo
     a.tile_meta = tile_meta; a.out0 = z; a.ldo = s.E;
     a.flat_rows = s.T; a.flat_bm = kFlatBM;
     return run_xw<true, EPI_F32>(a, cdiv(s.T, kBM), st);
-}
-
-bool mfma_route_fused_supported(const unipool_shape& s) {
-    return mfma_router_supported(s) && s.E <= kRouteMaxE;
-}
-
-// Logits GEMM with the NormRouter selection in its epilogue: one tile = 128 tokens x all experts.
-hipError_t mfma_route_fused(const unipool_shape& s, const void* x, const void* w, float* z, int32_t* topk_idx,
-                            float* topk_gate, int32_t* cnt_part, float* psum_part, hipStream_t st) {
-    static_assert(kFlatBM == kRouteRows, "the router tile holds one flat tile");
-    GemmArgs a = {};
-    a.X = (const bf16*)x; a.ldx = s.d_model;
-    a.W = (const bf16*)w; a.w_stride = 0; a.ldw = s.d_model;
-    a.K = s.d_model; a.N = s.E; a.n_tiles_n = 1;
-    a.out0 = z; a.ldo = s.E;
-    a.flat_rows = s.T; a.flat_bm = kFlatBM;
-    a.topk_idx = topk_idx; a.topk_gate = topk_gate; a.cnt_part = cnt_part; a.psum_part = psum_part;
-    a.topk = s.k; a.sigma_c = s.sigma * s.c; a.eps = s.eps; a.softmax = s.router == UNIPOOL_ROUTER_SOFTMAX;
-    return run_xw<true, EPI_ROUTE>(a, cdiv(s.T, kBM), st);
 }
 
 hipError_t mfma_ffn_gate_up(const unipool_shape& s, const void* x_perm, const int32_t* offsets,

@@ -42,6 +42,11 @@ hipError_t launch_estimate_c(int E, int k, const float* samples, int n, float* p
 hipError_t launch_distinct_experts(const int32_t* const* idx_layers, int L, int T, int k,
                                    int32_t* distinct, int32_t* part_sum, float* mean_out, hipStream_t st);
 
+// ---- router_fused.hip: logits on the matrix cores, scores, top-k and block statistics in one kernel -----
+bool router_fused_supported(const unipool_shape& s);
+hipError_t router_fused(const unipool_shape& s, const void* x, const void* w, float* z, int32_t* topk_idx,
+                        float* topk_gate, int32_t* cnt_part, float* psum_part, hipStream_t st);
+
 // ---- gemm_naive.hip: one thread per output element; any shape, both dtypes ---------
 hipError_t naive_logits(const unipool_shape& s, const void* x, const void* w, float* z, hipStream_t st);
 // slot_of_row != nullptr: x_perm is the un-permuted x and row r reads token slot_of_row[r] / k of it
@@ -69,9 +74,6 @@ hipError_t mfma_logits(const unipool_shape& s, const void* x, const void* w, flo
 hipError_t mfma_ffn_fwd(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
                         const void* wgu, const void* wd, void* a, void* b, void* h, void* y,
                         int32_t* tile_meta, hipStream_t st, const int32_t* slot_of_row = nullptr);
-bool mfma_route_fused_supported(const unipool_shape& s);
-hipError_t mfma_route_fused(const unipool_shape& s, const void* x, const void* w, float* z, int32_t* topk_idx,
-                            float* topk_gate, int32_t* cnt_part, float* psum_part, hipStream_t st);
 hipError_t mfma_ffn_gate_up(const unipool_shape& s, const void* x_perm, const int32_t* offsets,
                            const void* wgu, void* a, void* b, void* h, int32_t* tile_meta,
                            hipStream_t st, const int32_t* slot_of_row = nullptr);

@@ -71,7 +71,8 @@ def test_fast_path_reports_the_kernel_families(U):
         base.update(kw)
         return U.Shape(**base)
     assert U.fast_path(sh()) == 7                       # MFMA experts, MFMA router, fused router
-    assert U.fast_path(sh(E=512)) == 3                  # a pool beyond the fused router's 256 experts
+    assert U.fast_path(sh(E=512)) == 7                  # the largest pool the fused router takes
+    assert U.fast_path(sh(d_model=192)) == 3            # d_model not a multiple of 128: logits GEMM and selection in two kernels
     assert U.fast_path(sh(E=10)) == 1                   # E not a multiple of 8: plain router kernels
     assert U.fast_path(sh(dtype=U.F32)) == 0            # float mode: plain kernels throughout
     with pytest.raises(U.UniPoolError, match="k=9"):
