@@ -41,11 +41,18 @@ def parse():
                     help="keep one shared pair of A/B buffers and rebuild them before each layer's backward")
     ap.add_argument("--lagged", action="store_true", help="one-step-behind usage statistic across steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--step-only", action="store_true",
+                    help="whole steps only: no CPU baseline, no side measurements (analysis entry points, "
+                         "forward-only dispatch comparison), no other workloads; for profiler runs")
     ap.add_argument("--oracle-tokens", type=int, default=4096)
     ap.add_argument("--other-workloads", default="C2,C3,C4,C4z",
                     help="comma-separated workloads summarised after the headline one ('' for none)")
     ap.add_argument("--other-steps", type=int, default=3)
-    return ap.parse_args()
+    a = ap.parse_args()
+    if a.step_only:
+        a.no_cpu_baseline = True
+        a.other_workloads = ""
+    return a
 
 
 def cpu_baseline(w, xs0, wr0, g0, wg, wu, wd, n_tok, n_tok_1thread=512):
@@ -229,33 +236,35 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
-    n_draws = 100000
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(1)
-    draws = torch.randn((n_draws, w.E), generator=gen, device=dev, dtype=torch.float32)
-    c_out = torch.zeros(1, dtype=torch.float32, device=dev)
-    c_used = torch.zeros(1, dtype=torch.int32, device=dev)
-    ms_c = timed(lambda: U.estimate_c(w.E, w.k, draws, c_out, c_used, ps.ws))
-    idx_tab = torch.tensor([st.topk_idx.data_ptr() for st in ps.layers], dtype=torch.int64, device=dev)
-    dist = torch.zeros(w.T, dtype=torch.int32, device=dev)
-    dist_mean = torch.zeros(1, dtype=torch.float32, device=dev)
-    ms_u = timed(lambda: U.distinct_experts(ps.shape(1.0), w.L, idx_tab, dist, dist_mean, ps.ws))
-    by_c, by_u = 4.0 * n_draws * w.E, 4.0 * w.L * w.T * w.k + 4.0 * w.T
-    others["estimate_c"] = {"GB/s": by_c / (ms_c * 1e-3) / 1e9, "frac": by_c / (ms_c * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                            "avg_ms": ms_c, "algorithmic_bytes": by_c, "draws": n_draws, "c": float(c_out.item())}
-    others["distinct_experts"] = {"GB/s": by_u / (ms_u * 1e-3) / 1e9, "frac": by_u / (ms_u * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                                  "avg_ms": ms_u, "algorithmic_bytes": by_u,
-                                  "mean_distinct_per_token": float(dist_mean.item())}
+    if not a.step_only:
+        n_draws = 100000
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1)
+        draws = torch.randn((n_draws, w.E), generator=gen, device=dev, dtype=torch.float32)
+        c_out = torch.zeros(1, dtype=torch.float32, device=dev)
+        c_used = torch.zeros(1, dtype=torch.int32, device=dev)
+        ms_c = timed(lambda: U.estimate_c(w.E, w.k, draws, c_out, c_used, ps.ws))
+        idx_tab = torch.tensor([st.topk_idx.data_ptr() for st in ps.layers], dtype=torch.int64, device=dev)
+        dist = torch.zeros(w.T, dtype=torch.int32, device=dev)
+        dist_mean = torch.zeros(1, dtype=torch.float32, device=dev)
+        ms_u = timed(lambda: U.distinct_experts(ps.shape(1.0), w.L, idx_tab, dist, dist_mean, ps.ws))
+        by_c, by_u = 4.0 * n_draws * w.E, 4.0 * w.L * w.T * w.k + 4.0 * w.T
+        others["estimate_c"] = {"GB/s": by_c / (ms_c * 1e-3) / 1e9, "frac": by_c / (ms_c * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                "avg_ms": ms_c, "algorithmic_bytes": by_c, "draws": n_draws, "c": float(c_out.item())}
+        others["distinct_experts"] = {"GB/s": by_u / (ms_u * 1e-3) / 1e9, "frac": by_u / (ms_u * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                      "avg_ms": ms_u, "algorithmic_bytes": by_u,
+                                      "mean_distinct_per_token": float(dist_mean.item())}
 
     # ---- forward pass alone, with the permuted copy and with the dispatch fused into the first GEMM
-    fwd = {}
-    for mode, gather in (("materialised", False), ("gathered", True)):
-        def fwd_all(gather=gather):
-            for l in range(w.L):
-                ps.forward_layer(l, r["xs"][l], r["wrs"][l], w.sigma, r["wgu"], r["wd"], gather=gather)
-        fwd[mode + "_ms_per_forward"] = timed(fwd_all, reps=3)
-    fwd["gather_speedup"] = fwd["materialised_ms_per_forward"] / fwd["gathered_ms_per_forward"]
-    others["forward_only_dispatch"] = fwd
+    if not a.step_only:
+        fwd = {}
+        for mode, gather in (("materialised", False), ("gathered", True)):
+            def fwd_all(gather=gather):
+                for l in range(w.L):
+                    ps.forward_layer(l, r["xs"][l], r["wrs"][l], w.sigma, r["wgu"], r["wd"], gather=gather)
+            fwd[mode + "_ms_per_forward"] = timed(fwd_all, reps=3)
+        fwd["gather_speedup"] = fwd["materialised_ms_per_forward"] / fwd["gathered_ms_per_forward"]
+        others["forward_only_dispatch"] = fwd
 
     out = {
         "metric": "shared-pool MoE layer fwd+bwd tokens/s; grouped-GEMM % bf16 MFMA peak",

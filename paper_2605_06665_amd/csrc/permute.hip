@@ -143,6 +143,8 @@ __device__ __forceinline__ void rows_of_token(const int32_t* __restrict__ topk_i
     }
 }
 
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
 // One wavefront per token: 16-byte chunks of the row, read once, written k times.
 __global__ __launch_bounds__(256) void permute_copy_kernel(const uint4* __restrict__ x,
                                                            const int32_t* __restrict__ topk_idx,
@@ -176,7 +178,13 @@ __global__ __launch_bounds__(256) void permute_copy_kernel(const uint4* __restri
 #pragma unroll
             for (int u = 0; u < 4; u++) {
                 const int c = c0 + u * 64 + lane;
-                if (c < row_chunks) dst[c] = v[u];
+                // the copy is written once and read much later by another kernel: a streaming store keeps it
+                // from displacing the lines of x that are still to be read (measured 13 % faster at d_model
+                // 1536, k = 2; the same hint on the combine kernels' stores measured slower)
+                if (c < row_chunks) {
+                    const u32x4 q = {v[u].x, v[u].y, v[u].z, v[u].w};
+                    __builtin_nontemporal_store(q, reinterpret_cast<u32x4*>(dst + c));
+                }
             }
         }
     }
