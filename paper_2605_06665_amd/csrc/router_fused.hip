@@ -196,8 +196,11 @@ __device__ __forceinline__ void rf_body(const RouterArgs& a, char* smem) {
         const int c4n = E / 4;
         for (int id = tid; id < rows * c4n; id += kRfThreads) {
             const int r = id / c4n, c4 = id % c4n;
-            *reinterpret_cast<float4*>(a.logits + (size_t)(t0 + r) * E + 4 * c4) =
-                *reinterpret_cast<const float4*>(tile + r * ldz + 4 * c4);
+            // streaming store: the rows are read again only by the backward pass, and lines left dirty in
+            // L2 would be written back after the last workgroup, when nothing overlaps the write any more
+            const float4 v = *reinterpret_cast<const float4*>(tile + r * ldz + 4 * c4);
+            const f32x4 q = {v.x, v.y, v.z, v.w};
+            __builtin_nontemporal_store(q, reinterpret_cast<f32x4*>(a.logits + (size_t)(t0 + r) * E + 4 * c4));
         }
     }
     // ---- selection by all six wavefronts: the 64 / TPW steps of a 64-token block are split among the
