@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "unipool.h"
 
 namespace unipool {
@@ -26,6 +28,25 @@ int set_error(int code, const char* fmt, ...);
 int check_hip(hipError_t e, const char* what);
 // Range and alignment checks every entry point runs on its shape before anything is launched.
 int validate_shape(const unipool_shape* s, const char* fn);
+
+// ---- top-k as a compile-time constant (host) --------------------------------
+// The per-token kernels loop over the k copies of a token; with k known at compile time these loops unroll,
+// the rows of the copies sit in registers and their loads are in flight together.
+// Calls f with k as a compile-time constant (1 <= k <= kMaxK, checked at the boundary).
+template <class F>
+inline void with_top_k(int k, F f) {
+    static_assert(kMaxK == 8, "one case per admissible k");
+    switch (k) {
+        case 1: f(std::integral_constant<int, 1>{}); break;
+        case 2: f(std::integral_constant<int, 2>{}); break;
+        case 3: f(std::integral_constant<int, 3>{}); break;
+        case 4: f(std::integral_constant<int, 4>{}); break;
+        case 5: f(std::integral_constant<int, 5>{}); break;
+        case 6: f(std::integral_constant<int, 6>{}); break;
+        case 7: f(std::integral_constant<int, 7>{}); break;
+        default: f(std::integral_constant<int, 8>{}); break;
+    }
+}
 
 // ---- scalar conversions (device) --------------------------------------------
 __device__ __forceinline__ float to_f32(float v) { return v; }

@@ -126,43 +126,54 @@ __global__ __launch_bounds__(256) void permute_scan_kernel(const int32_t* __rest
     }
 }
 
-// Rows of token t (lane-uniform): lane l holds the selections of token chunk*64 + l.
-__device__ __forceinline__ void rows_of_token(const int32_t* __restrict__ topk_idx, int t, int T, int E, int k,
-                                              const int32_t* __restrict__ chunk_base, int lane, int* rows) {
+// Rows of token t (lane-uniform): lane l holds the selections of token chunk*64 + l.  K = top-k at compile
+// time: the loops unroll, so the K selections are loaded together and so are the K chunk bases.
+template <int K>
+__device__ __forceinline__ void rows_of_token(const int32_t* __restrict__ topk_idx, int t, int T, int E,
+                                              const int32_t* __restrict__ chunk_base, int lane, int (&rows)[K]) {
     const int chunk = t >> 6, tl = t & 63;
     const int to = chunk * 64 + lane;
-    int other[kMaxK];
-    for (int j = 0; j < k; j++) other[j] = to < T ? topk_idx[(size_t)to * k + j] : -1;
+    int other[K];
+#pragma unroll
+    for (int j = 0; j < K; j++) other[j] = to < T ? topk_idx[(size_t)to * K + j] : -1;
     const unsigned long long below = (1ull << tl) - 1ull;
-    for (int j = 0; j < k; j++) {
+    int base[K], rank[K];
+#pragma unroll
+    for (int j = 0; j < K; j++) {
         const int e = __shfl(other[j], tl, 64);                     // this token's j-th expert
+        base[j] = chunk_base[(size_t)chunk * E + e];
         bool hit = false;
-        for (int i = 0; i < k; i++) hit |= other[i] == e;
+#pragma unroll
+        for (int i = 0; i < K; i++) hit |= other[i] == e;
         const unsigned long long sel = __ballot(hit);               // tokens of the chunk that selected e
-        rows[j] = chunk_base[(size_t)chunk * E + e] + __popcll(sel & below);
+        rank[j] = __popcll(sel & below);
     }
+#pragma unroll
+    for (int j = 0; j < K; j++) rows[j] = base[j] + rank[j];
 }
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 // One wavefront per token: 16-byte chunks of the row, read once, written k times.
+template <int K>
 __global__ __launch_bounds__(256) void permute_copy_kernel(const uint4* __restrict__ x,
                                                            const int32_t* __restrict__ topk_idx,
                                                            const int32_t* __restrict__ chunk_base,
-                                                           int T, int E, int k, int row_chunks,
+                                                           int T, int E, int row_chunks,
                                                            uint4* __restrict__ x_perm,
                                                            int32_t* __restrict__ row_of_slot,
                                                            int32_t* __restrict__ slot_of_row) {
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
-    int rows[kMaxK];
-    rows_of_token(topk_idx, t, T, E, k, chunk_base, lane, rows);
-    if (lane < k) {
+    int rows[K];
+    rows_of_token<K>(topk_idx, t, T, E, chunk_base, lane, rows);
+    if (lane < K) {
         int r = rows[0];
-        for (int j = 1; j < k; j++) r = lane == j ? rows[j] : r;
-        row_of_slot[(size_t)t * k + lane] = r;
-        slot_of_row[r] = t * k + lane;
+#pragma unroll
+        for (int j = 1; j < K; j++) r = lane == j ? rows[j] : r;
+        row_of_slot[(size_t)t * K + lane] = r;
+        slot_of_row[r] = t * K + lane;
     }
     if (x_perm == nullptr) return;                 // index maps only
     const uint4* src = x + (size_t)t * row_chunks;
@@ -173,7 +184,8 @@ __global__ __launch_bounds__(256) void permute_copy_kernel(const uint4* __restri
             const int c = c0 + u * 64 + lane;
             if (c < row_chunks) v[u] = src[c];
         }
-        for (int j = 0; j < k; j++) {
+#pragma unroll
+        for (int j = 0; j < K; j++) {
             uint4* dst = x_perm + (size_t)rows[j] * row_chunks;
 #pragma unroll
             for (int u = 0; u < 4; u++) {
@@ -191,21 +203,23 @@ __global__ __launch_bounds__(256) void permute_copy_kernel(const uint4* __restri
 }
 
 // Rows whose byte length is not a multiple of 16 (only possible in float mode with odd d).
+template <int K>
 __global__ __launch_bounds__(64) void permute_copy_scalar_kernel(const uint32_t* __restrict__ x,
                                                                  const int32_t* __restrict__ topk_idx,
                                                                  const int32_t* __restrict__ chunk_base,
-                                                                 int T, int E, int k, int row_words,
+                                                                 int T, int E, int row_words,
                                                                  uint32_t* __restrict__ x_perm,
                                                                  int32_t* __restrict__ row_of_slot,
                                                                  int32_t* __restrict__ slot_of_row) {
     const int lane = threadIdx.x;
     const int t = blockIdx.x;
-    int rows[kMaxK];
-    rows_of_token(topk_idx, t, T, E, k, chunk_base, lane, rows);
-    for (int j = 0; j < k; j++) {
+    int rows[K];
+    rows_of_token<K>(topk_idx, t, T, E, chunk_base, lane, rows);
+#pragma unroll
+    for (int j = 0; j < K; j++) {
         if (lane == 0) {
-            row_of_slot[(size_t)t * k + j] = rows[j];
-            slot_of_row[rows[j]] = t * k + j;
+            row_of_slot[(size_t)t * K + j] = rows[j];
+            slot_of_row[rows[j]] = t * K + j;
         }
         if (x_perm == nullptr) continue;           // index maps only
         for (int c = lane; c < row_words; c += 64)
@@ -225,15 +239,18 @@ hipError_t launch_permute(const unipool_shape& s, const void* x, const int32_t* 
     permute_hist_kernel<<<nblocks, 256, lds, st>>>(topk_idx, s.T, s.E, s.k, chunk_hist);
     permute_scan_kernel<<<s.E, 256, 0, st>>>(counts, s.E, nchunks, expert_offsets, chunk_hist);
     const size_t row_bytes = (size_t)s.d_model * (s.dtype == UNIPOOL_BF16 ? 2 : 4);
-    if (row_bytes % 16 == 0) {
-        permute_copy_kernel<<<cdiv(s.T, 4), 256, 0, st>>>((const uint4*)x, topk_idx, chunk_hist, s.T, s.E, s.k,
-                                                          (int)(row_bytes / 16), (uint4*)x_perm, row_of_slot,
-                                                          slot_of_row);
-    } else {
-        permute_copy_scalar_kernel<<<s.T, 64, 0, st>>>((const uint32_t*)x, topk_idx, chunk_hist, s.T, s.E, s.k,
-                                                       (int)(row_bytes / 4), (uint32_t*)x_perm, row_of_slot,
-                                                       slot_of_row);
-    }
+    with_top_k(s.k, [&](auto kc) {
+        constexpr int K = decltype(kc)::value;
+        if (row_bytes % 16 == 0) {
+            permute_copy_kernel<K><<<cdiv(s.T, 4), 256, 0, st>>>((const uint4*)x, topk_idx, chunk_hist, s.T, s.E,
+                                                                 (int)(row_bytes / 16), (uint4*)x_perm, row_of_slot,
+                                                                 slot_of_row);
+        } else {
+            permute_copy_scalar_kernel<K><<<s.T, 64, 0, st>>>((const uint32_t*)x, topk_idx, chunk_hist, s.T, s.E,
+                                                              (int)(row_bytes / 4), (uint32_t*)x_perm, row_of_slot,
+                                                              slot_of_row);
+        }
+    });
     return hipGetLastError();
 }
 

@@ -113,6 +113,8 @@ __global__ __launch_bounds__(256) void route_bwd_dz_kernel(
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int grp = lane / GS, sl = lane % GS;
+    const auto add = [](float a, float b) { return a + b; };
+    const auto fmx = [](float a, float b) { return fmaxf(a, b); };
     float coef[VPL];
 #pragma unroll
     for (int i = 0; i < VPL; i++) {
@@ -135,14 +137,20 @@ __global__ __launch_bounds__(256) void route_bwd_dz_kernel(
             ss += z[i] * z[i];
             ds[i] = coef[i];
         }
+        ss = group_reduce_f<GS>(ss, add);
+        // the k selections and their gate gradients are requested together, then applied in slot order
+        int selv[kMaxK];
+        float gdv[kMaxK];
 #pragma unroll
-        for (int o = GS / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-        for (int j = 0; j < k; j++) {
-            const int sel = topk_idx[(size_t)tc * k + j];
-            const float gd = dgate[(size_t)tc * k + j];
+        for (int j = 0; j < kMaxK; j++) {
+            selv[j] = j < k ? topk_idx[(size_t)tc * k + j] : -1;
+            gdv[j] = j < k ? dgate[(size_t)tc * k + j] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < kMaxK; j++) {
 #pragma unroll
             for (int i = 0; i < VPL; i++)
-                if (sel == sl + GS * i) ds[i] += gd;
+                if (selv[j] == sl + GS * i) ds[i] += gdv[j];
         }
         if (softmax) {
             // dz_j = p_j (ds_j - <ds, p>) with p = softmax(z); sigma takes no part
@@ -150,8 +158,7 @@ __global__ __launch_bounds__(256) void route_bwd_dz_kernel(
 #pragma unroll
             for (int i = 0; i < VPL; i++)
                 if (sl + GS * i < E) zmax = fmaxf(zmax, z[i]);
-#pragma unroll
-            for (int o = GS / 2; o > 0; o >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, o, 64));
+            zmax = group_reduce_f<GS>(zmax, fmx);
             float pr[VPL];
             float se = 0.f;
 #pragma unroll
@@ -159,8 +166,7 @@ __global__ __launch_bounds__(256) void route_bwd_dz_kernel(
                 pr[i] = (sl + GS * i < E) ? expf(z[i] - zmax) : 0.f;
                 se += pr[i];
             }
-#pragma unroll
-            for (int o = GS / 2; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
+            se = group_reduce_f<GS>(se, add);
             const float inv_se = 1.0f / se;
             float dotp = 0.f;
 #pragma unroll
@@ -168,8 +174,7 @@ __global__ __launch_bounds__(256) void route_bwd_dz_kernel(
                 pr[i] *= inv_se;
                 dotp += ds[i] * pr[i];
             }
-#pragma unroll
-            for (int o = GS / 2; o > 0; o >>= 1) dotp += __shfl_xor(dotp, o, 64);
+            dotp = group_reduce_f<GS>(dotp, add);
             if (live) {
 #pragma unroll
                 for (int i = 0; i < VPL; i++) {
@@ -190,8 +195,7 @@ __global__ __launch_bounds__(256) void route_bwd_dz_kernel(
             dzh[i] = (zh > 0.f) ? ds[i] * sigma * c : 0.f;
             dot += dzh[i] * z[i];
         }
-#pragma unroll
-        for (int o = GS / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+        dot = group_reduce_f<GS>(dot, add);
         const float back = (n > 0.f) ? dot * inv * inv / n : 0.f;
         if (live) {
 #pragma unroll
