@@ -194,6 +194,17 @@ def run_workload(name, a, steps, warmup, keep=False):
     ps.events = []
     ps.timing = False
     res = dict(w=w, ms_step=dt / steps * 1e3, agg=agg, ps=ps)
+    if not a.step_only and not a.lagged:
+        # the same step recorded once into a HIP graph and replayed: what the launches cost on the host side
+        graph = ps.capture(xs, wrs, sigmas, wgu, wd, gs)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        res["ms_step_graph"] = (time.perf_counter() - t0) / steps * 1e3
+        del graph
     if keep:
         res.update(xs=xs, wrs=wrs, gs=gs, wg=wg, wu=wu, wd=wd, wgu=wgu)
     return res
@@ -266,6 +277,9 @@ def main():
         fwd["gather_speedup"] = fwd["materialised_ms_per_forward"] / fwd["gathered_ms_per_forward"]
         others["forward_only_dispatch"] = fwd
 
+    if "ms_step_graph" in r:
+        others["step_as_graph"] = {"ms_per_step": r["ms_step_graph"], "eager_ms_per_step": ms_step,
+                                   "note": "the same step replayed from a HIP graph; `value` is the eager step"}
     out = {
         "metric": "shared-pool MoE layer fwd+bwd tokens/s; grouped-GEMM % bf16 MFMA peak",
         "value": w.L * w.T / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
@@ -297,7 +311,7 @@ def main():
             xo, oo = roofline_of(wo, a, ro["ps"], ro["agg"], a.other_steps)
             summary[name] = {
                 "workload": wo.name, "ms_per_step": ro["ms_step"], "tokens/s": wo.L * wo.T / (ro["ms_step"] * 1e-3),
-                "steps": a.other_steps,
+                "steps": a.other_steps, "ms_per_step_as_graph": ro.get("ms_step_graph"),
                 "gemm_xw_frac_mfma": xo["frac"], "gemm_xw_avg_launch_ms": xo["avg_launch_ms"],
                 "gemm_xw_floor": xo["floor"],
                 "gemm_all_frac_mfma": oo["grouped_gemm_all"]["frac"],

@@ -225,6 +225,23 @@ class PoolStep:
         self.end_backward()
 
 
+    # ------------------------------------------------------------------ the step as a HIP graph
+    def capture(self, xs, w_routers, sigmas, w_gate_up, w_down, grad_outs):
+        """Records one whole step into a HIP graph and returns it (replay() launches it).  The entry points
+        allocate nothing, never synchronise and record no memset, so a step is a fixed chain of kernel
+        launches on the caller's stream; the graph reads and writes the very buffers given here and the
+        step's own state.  Not for the lagged statistic, whose buffers change from one micro-batch to the
+        next, nor with event timing on."""
+        assert not self.lagged and not self.timing, "a recorded step has fixed buffers and no events"
+        # every kernel must have run once outside the recording: their first launch sets function attributes
+        self.step(xs, w_routers, sigmas, w_gate_up, w_down, grad_outs)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step(xs, w_routers, sigmas, w_gate_up, w_down, grad_outs)
+        return graph
+
+
 class PoolGroups:
     """Sharing scope G (Sec. 5.4): the layers are cut into G groups over depth and every group has a
     pool, a pool loss and a weight gradient of its own.  One PoolStep per group; a step runs them one
