@@ -397,15 +397,16 @@ def pool_step(xs, w_routers, w_gate, w_up, w_down, grad_outs, k, sigmas, c, eps,
                 loss=loss, loss_layers=loss_layers, coef=coef, dw_gate=dwg, dw_up=dwu, dw_down=dwd)
 
 
-def pool_groups_step(groups, k, c, eps, alpha):
+def pool_groups_step(groups, k, c, eps, alpha, router="norm"):
     """Sharing scope G (Sec. 5.4): the layers are cut into G groups over depth, every group
     routes into a pool of its own and carries its own pool loss (Eq. 5 over the group's
     layers); G = 1 is the fully shared pool, one layer per group is the layer-private MoE
-    with the loss of Eq. 3.  `groups` is a list of dicts with keys xs, w_routers, w_gate,
-    w_up, w_down, grad_outs, sigmas.  Returns the per-group pool_step results and the sum
-    of the group losses."""
+    with the loss of Eq. 3 (with router = "softmax" and k = 1 that is the vanilla MoE of Eq. 1
+    that the paper compares against).  `groups` is a list of dicts with keys xs, w_routers,
+    w_gate, w_up, w_down, grad_outs, sigmas.  Returns the per-group pool_step results and the
+    sum of the group losses."""
     results = [pool_step(g["xs"], g["w_routers"], g["w_gate"], g["w_up"], g["w_down"], g["grad_outs"],
-                         k, g["sigmas"], c, eps, alpha) for g in groups]
+                         k, g["sigmas"], c, eps, alpha, router=router) for g in groups]
     return results, float(sum(r["loss"] for r in results))
 
 

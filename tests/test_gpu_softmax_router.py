@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 
 from oracle import unipool_oracle as O
+from synth import workloads as W
 from tests.gpu_util import TOL, check_selection, dev, host, rel_err, round_act
 from tests.test_gpu_parity import CASES, empty, lib, oracle_case, pack_gate_up, shape_of, workspace
 
@@ -93,6 +94,55 @@ def test_whole_step_softmax(name):
         assert rel_err(host(st.d_w_router), bw["dw_router"]) <= tol, "dw_router"
     assert rel_err(host(ps.d_w_gate_up), np.concatenate([ref["dw_gate"], ref["dw_up"]], axis=1)) <= tol
     assert rel_err(host(ps.d_w_down), ref["dw_down"]) <= tol
+
+
+VANILLA = {
+    "f32": W.Workload("vanilla-f32", L=3, E=8, d=48, f=40, k=1, T=210, dtype="f32", seed=71, c=1.0),
+    "bf16": W.Workload("vanilla-bf16", L=4, E=8, d=128, f=192, k=1, T=1500, dtype="bf16", seed=72, c=1.0),
+}
+
+
+@pytest.mark.parametrize("kind", list(VANILLA))
+def test_vanilla_moe_layer_private_experts_top1_softmax(kind):
+    """The comparison system of the paper (Eq. 1, Eq. 3; 8 experts per layer, top-1, softmax router): one group
+    per layer, each with experts, loss and weight gradient of its own, through the same entry points."""
+    import torch
+    from paper_2605_06665_amd.pipeline import PoolGroups
+    w, U = VANILLA[kind], lib()
+    xs = [W.gen_x(w, l) for l in range(w.L)]
+    wrs = [W.gen_w_router(w, l) for l in range(w.L)]
+    gs = [W.gen_grad_out(w, l) for l in range(w.L)]
+    pools = [W.gen_pool_weights(w.scaled(seed=w.seed + 100 * l)) for l in range(w.L)]
+    sigmas = [1.0] * w.L
+    pg = PoolGroups(w.L, w.T, w.d, w.f, w.E, w.k, w.L, U.BF16 if w.dtype == "bf16" else U.F32, w.c, w.eps, w.alpha,
+                    router="softmax")
+    pg.step([dev(x, w.dtype) for x in xs], [dev(x, w.dtype) for x in wrs], sigmas,
+            [dev(pack_gate_up(p[0], p[1]), w.dtype) for p in pools], [dev(p[2], w.dtype) for p in pools],
+            [dev(x, w.dtype) for x in gs])
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    total = 0.0
+    for l in range(w.L):
+        ps = pg.groups[l]
+        z = O.router_logits(xs[l], wrs[l])
+        _, merged = check_selection(z, O.topk_select(z, w.k), host(ps.layers[0].topk_idx), w.k)
+        ref = O.pool_step([xs[l]], [wrs[l]], *pools[l], [gs[l]], w.k, [1.0], w.c, w.eps, w.alpha, idxs=[merged],
+                          router="softmax")
+        total += ref["loss"]
+        assert np.array_equal(host(ps.counts), ref["counts"])
+        assert abs(float(host(ps.loss)[0]) - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+        assert rel_err(host(ps.layers[0].out), ref["fw"][0]["out"]) <= tol
+        assert rel_err(host(ps.layers[0].dx), ref["bw"][0]["dx"]) <= tol
+        assert rel_err(host(ps.layers[0].d_w_router), ref["bw"][0]["dw_router"]) <= tol
+        assert rel_err(host(ps.d_w_gate_up), np.concatenate([ref["dw_gate"], ref["dw_up"]], axis=1)) <= tol
+        assert rel_err(host(ps.d_w_down), ref["dw_down"]) <= tol
+    # the same groups through the oracle's own group step give the same total
+    if all(np.array_equal(host(pg.groups[l].layers[0].topk_idx).ravel(),
+                          np.argmax(O.router_logits(xs[l], wrs[l]), axis=1)) for l in range(w.L)):
+        groups = [dict(xs=[xs[l]], w_routers=[wrs[l]], w_gate=pools[l][0], w_up=pools[l][1], w_down=pools[l][2],
+                       grad_outs=[gs[l]], sigmas=[1.0]) for l in range(w.L)]
+        _, ref_total = O.pool_groups_step(groups, w.k, w.c, w.eps, w.alpha, router="softmax")
+        assert abs(ref_total - total) <= 1e-12 * abs(total)
 
 
 def test_unknown_router_kind_is_rejected():

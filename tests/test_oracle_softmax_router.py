@@ -95,3 +95,38 @@ def test_router_backward_against_autograd():
     obj.backward()
     assert np.allclose(tx.grad.numpy(), dx, atol=1e-12) and np.allclose(tw.grad.numpy(), dw, atol=1e-12)
     assert dsig == 0.0 and np.allclose(dz.sum(axis=1), 0.0, atol=1e-13)      # softmax gradients sum to zero
+
+
+def test_vanilla_moe_is_one_layer_per_group_with_the_softmax_router():
+    """The comparison system of Eq. 1 / Eq. 3: private experts per layer, top-1 softmax router, per-layer loss.
+    Its loss is alpha E sum_i f_i P_i by hand for every layer, its output the selected expert's output times
+    the selected probability, and no weight gradient crosses the layers."""
+    rng = np.random.default_rng(7)
+    L, T, d, f, E = 3, 60, 10, 12, 5
+    xs = [rng.standard_normal((T, d)) for _ in range(L)]
+    gs = [rng.standard_normal((T, d)) for _ in range(L)]
+    wrs = [rng.standard_normal((E, d)) for _ in range(L)]
+    pools = [tuple(rng.standard_normal(s) * 0.3 for s in ((E, f, d), (E, f, d), (E, d, f))) for _ in range(L)]
+    alpha = 0.02
+    groups = [dict(xs=[xs[l]], w_routers=[wrs[l]], w_gate=pools[l][0], w_up=pools[l][1], w_down=pools[l][2],
+                   grad_outs=[gs[l]], sigmas=[1.0]) for l in range(L)]
+    res, total = O.pool_groups_step(groups, 1, 1.0, 1e-6, alpha, router="softmax")
+    hand_total = 0.0
+    for l in range(L):
+        z = xs[l] @ wrs[l].T
+        p = np.exp(z - z.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        sel = np.argmax(z, axis=1)
+        fvec = np.bincount(sel, minlength=E) / T
+        hand = alpha * E * float(np.sum(fvec * p.mean(axis=0)))
+        assert res[l]["loss"] == pytest.approx(hand, rel=1e-12)
+        hand_total += hand
+        # token 0 by hand: the selected expert's SwiGLU output times its probability
+        e = sel[0]
+        a, b = pools[l][0][e] @ xs[l][0], pools[l][1][e] @ xs[l][0]
+        y = pools[l][2][e] @ (a / (1.0 + np.exp(-a)) * b)
+        assert np.allclose(res[l]["fw"][0]["out"][0], p[0, e] * y, atol=1e-12)
+        # experts that no token of this layer selected get no gradient
+        idle = np.setdiff1d(np.arange(E), sel)
+        assert not np.any(res[l]["dw_down"][idle])
+    assert total == pytest.approx(hand_total, rel=1e-12)
