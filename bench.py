@@ -196,15 +196,20 @@ def run_workload(name, a, steps, warmup, keep=False):
     res = dict(w=w, ms_step=dt / steps * 1e3, agg=agg, ps=ps)
     if not a.step_only and not a.lagged:
         # the same step recorded once into a HIP graph and replayed: what the launches cost on the host side
-        graph = ps.capture(xs, wrs, sigmas, wgu, wd, gs)
-        graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
+        # (a side figure: if recording fails the headline stands and the reason is reported in its place)
+        try:
+            graph = ps.capture(xs, wrs, sigmas, wgu, wd, gs)
             graph.replay()
-        torch.cuda.synchronize()
-        res["ms_step_graph"] = (time.perf_counter() - t0) / steps * 1e3
-        del graph
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            res["ms_step_graph"] = (time.perf_counter() - t0) / steps * 1e3
+            del graph
+        except Exception as exc:          # noqa: BLE001
+            res["graph_error"] = "%s: %s" % (type(exc).__name__, exc)
+            torch.cuda.synchronize()
     if keep:
         res.update(xs=xs, wrs=wrs, gs=gs, wg=wg, wu=wu, wd=wd, wgu=wgu)
     return res
@@ -277,6 +282,8 @@ def main():
         fwd["gather_speedup"] = fwd["materialised_ms_per_forward"] / fwd["gathered_ms_per_forward"]
         others["forward_only_dispatch"] = fwd
 
+    if "graph_error" in r:
+        others["step_as_graph"] = {"error": r["graph_error"]}
     if "ms_step_graph" in r:
         others["step_as_graph"] = {"ms_per_step": r["ms_step_graph"], "eager_ms_per_step": ms_step,
                                    "note": "the same step replayed from a HIP graph; `value` is the eager step"}
